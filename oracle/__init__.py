@@ -1,0 +1,156 @@
+"""fp64 CPU oracle for the dual trit-plane linear layer -- TEST INFRASTRUCTURE.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It shares nothing with the HIP library and never imports it.
+
+Two independent evaluations of the layer (paper, Eq. 1-2 with the group-wise
+scales of paragraph "Batch Processing"):
+
+* forward()       -- C, scale-after-plane-product order of Eq. 1 (ptqtp_oracle.c)
+* forward_dense() -- numpy, "dequantization" order: rebuild W^ then a library
+                     matmul (Sec. "Inference Efficiency" names both orders)
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ptqtp_oracle.c")
+_LIB = os.path.join(_HERE, "libptqtp_oracle.so")
+_lib = None
+
+OK, ERR_SHAPE, ERR_TRIT, ERR_CODE = 0, 1, 2, 3
+
+
+class OracleError(ValueError):
+    def __init__(self, code: int):
+        super().__init__({1: "bad shape", 2: "trit outside {-1,0,1}", 3: "unused 2-bit code"}.get(code, str(code)))
+        self.code = code
+
+
+def build(force: bool = False) -> str:
+    """Compile ptqtp_oracle.c with gcc (-O2, OpenMP for the row loop)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+                               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        lib.ptqtp_oracle_half_to_double.restype = ctypes.c_double
+        lib.ptqtp_oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.ptqtp_oracle_forward_f64x.restype = i32
+        lib.ptqtp_oracle_forward_f64x.argtypes = [p, p, p, p, p, i64, i64, i64, i64, p, p, i32]
+        lib.ptqtp_oracle_forward.restype = i32
+        lib.ptqtp_oracle_forward.argtypes = [p, p, p, p, p, p, i64, i64, i64, i64, p, p, i32]
+        lib.ptqtp_oracle_pack_canonical.restype = i32
+        lib.ptqtp_oracle_pack_canonical.argtypes = [p, i64, i64, p]
+        lib.ptqtp_oracle_unpack_canonical.restype = i32
+        lib.ptqtp_oracle_unpack_canonical.argtypes = [p, i64, i64, p]
+        lib.ptqtp_oracle_model_bits.restype = i64
+        lib.ptqtp_oracle_model_bits.argtypes = [i64, i64, i64]
+        _lib = lib
+    return _lib
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def half_to_double(bits: int) -> float:
+    return _load().ptqtp_oracle_half_to_double(int(bits) & 0xFFFF)
+
+
+def forward(T1, T2, a1, a2, x, group: int = 128, threads: int = 1, want_bound: bool = True):
+    """y, B = forward(...).  T int8 [N,K]; a float16 [N,K/group]; x float16 [M,K]
+    (or float64 [M,K] for linearity checks).  Returns float64 [M,N] arrays."""
+    lib = _load()
+    T1, pT1 = _c(T1, np.int8)
+    T2, pT2 = _c(T2, np.int8)
+    N, K = T1.shape
+    if T2.shape != (N, K):
+        raise OracleError(ERR_SHAPE)
+    a1 = np.ascontiguousarray(a1)
+    a2 = np.ascontiguousarray(a2)
+    if a1.dtype != np.float16 or a2.dtype != np.float16:
+        raise TypeError("scales must be float16")
+    if K % group or a1.shape != (N, K // group) or a2.shape != (N, K // group):
+        raise OracleError(ERR_SHAPE)
+    x = np.ascontiguousarray(x)
+    if x.ndim == 1:
+        x = x[None, :]
+    M = x.shape[0]
+    if x.shape[1] != K:
+        raise OracleError(ERR_SHAPE)
+    y = np.empty((M, N), dtype=np.float64)
+    b = np.empty((M, N), dtype=np.float64) if want_bound else None
+    pb = b.ctypes.data_as(ctypes.c_void_p) if want_bound else None
+    pa1 = a1.view(np.uint16).ctypes.data_as(ctypes.c_void_p)
+    pa2 = a2.view(np.uint16).ctypes.data_as(ctypes.c_void_p)
+    py = y.ctypes.data_as(ctypes.c_void_p)
+    if x.dtype == np.float16:
+        scratch = np.empty((M, K), dtype=np.float64)
+        rc = lib.ptqtp_oracle_forward(pT1, pT2, pa1, pa2, x.view(np.uint16).ctypes.data_as(ctypes.c_void_p),
+                                      scratch.ctypes.data_as(ctypes.c_void_p), M, N, K, group, py, pb, threads)
+    elif x.dtype == np.float64:
+        rc = lib.ptqtp_oracle_forward_f64x(pT1, pT2, pa1, pa2, x.ctypes.data_as(ctypes.c_void_p),
+                                           M, N, K, group, py, pb, threads)
+    else:
+        raise TypeError("x must be float16 or float64")
+    if rc != OK:
+        raise OracleError(rc)
+    return y, b
+
+
+def reconstruct_dense(T1, T2, a1, a2, group: int = 128) -> np.ndarray:
+    """W^ = alpha1 (.) T1 + alpha2 (.) T2 as float64 [N,K] (Eq. 2, group-wise scales).
+    Exact: each entry is a sum of two binary16-valued numbers."""
+    T1 = np.asarray(T1, dtype=np.float64)
+    T2 = np.asarray(T2, dtype=np.float64)
+    A1 = np.repeat(np.asarray(a1, dtype=np.float64), group, axis=1)
+    A2 = np.repeat(np.asarray(a2, dtype=np.float64), group, axis=1)
+    return A1 * T1 + A2 * T2
+
+
+def forward_dense(T1, T2, a1, a2, x, group: int = 128) -> np.ndarray:
+    """Second, independent evaluation: rebuild W^ and use the library matmul."""
+    W = reconstruct_dense(T1, T2, a1, a2, group)
+    x = np.asarray(x, dtype=np.float64)
+    if x.ndim == 1:
+        x = x[None, :]
+    return x @ W.T
+
+
+def pack_canonical(T) -> np.ndarray:
+    T, pT = _c(T, np.int8)
+    N, K = T.shape
+    out = np.empty((N, K // 4), dtype=np.uint8)
+    rc = _load().ptqtp_oracle_pack_canonical(pT, N, K, out.ctypes.data_as(ctypes.c_void_p))
+    if rc != OK:
+        raise OracleError(rc)
+    return out
+
+
+def unpack_canonical(packed, K: int) -> np.ndarray:
+    packed, pp = _c(packed, np.uint8)
+    N = packed.shape[0]
+    T = np.empty((N, K), dtype=np.int8)
+    rc = _load().ptqtp_oracle_unpack_canonical(pp, N, K, T.ctypes.data_as(ctypes.c_void_p))
+    if rc != OK:
+        raise OracleError(rc)
+    return T
+
+
+def model_bits(n: int, d: int, group: int = 128) -> int:
+    return int(_load().ptqtp_oracle_model_bits(n, d, group))
