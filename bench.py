@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the PTQTP decode hot path on one MI355X.
+
+A step is one decode step through the linear layers of an 8B-shaped decoder
+stack at batch 1: `--layers` (default 32) layers x the seven linears q, k, v,
+o, gate, up, down, every linear with its own packed blob and its own x, run
+back to back on one stream.  The shapes are BASELINE config 1; walking 32
+distinct layer copies (3.7 GB of packed planes + scales) keeps every launch
+cold in HBM instead of warm in the 256 MB Infinity Cache.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(N: int, K: int, M: int = 1, group: int = 128) -> int:
+    """Bytes one call has to move: 2-bit planes + fp16 scales (appendix memory model,
+    0.53125 B per weight at G = 128) + fp16 x + fp32 y."""
+    return N * K // 2 + 4 * N * (K // group) + 2 * M * K + 4 * M * N
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
+                    help="graph: one hipGraph replay per step; eager: 7*layers library calls per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-shape", action="store_true", help="also time every shape on its own (hot and cold)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path needs no second device); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2509_16989_amd as ptq
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    names = workloads.LINEAR_ORDER
+    shapes = workloads.SHAPES_8B
+
+    # ---- build the stack: generate on the host (seeded recipe), pack on the device ----------
+    t0 = time.time()
+    pool = ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1))
+    jobs = [(layer, name) for layer in range(args.layers) for name in names]
+
+    def gen(job):
+        layer, name = job
+        return workloads.linear_8b(name, layer)
+
+    blobs, xs, ys = [], [], []
+    layer0 = None
+    window = 14
+    pending = [pool.submit(gen, j) for j in jobs[:window]]
+    nxt = window
+    for idx, job in enumerate(jobs):
+        lin = pending.pop(0).result()
+        if nxt < len(jobs):
+            pending.append(pool.submit(gen, jobs[nxt]))
+            nxt += 1
+        N, K = lin["N"], lin["K"]
+        blob = ptq.ptqtp_pack(*(torch.from_numpy(lin[k]).to(dev) for k in ("T1", "T2", "a1", "a2")), check=False)
+        blobs.append(blob)
+        xs.append(torch.from_numpy(workloads.x_for(job[1], 1, K, 1, job[0])).to(dev).reshape(-1))
+        ys.append(torch.empty((1, N), dtype=torch.float32, device=dev))
+        if job[0] == 0:
+            layer0 = layer0 or {}
+            layer0[job[1]] = lin
+        if idx % 28 == 27:
+            print(f"[bench] packed {idx + 1}/{len(jobs)} linears ({time.time() - t0:.0f} s)", file=sys.stderr, flush=True)
+    pool.shutdown()
+    torch.cuda.synchronize()
+    dims = [shapes[name] for _, name in jobs]
+    bytes_step = sum(algorithmic_bytes(n, k) for n, k in dims)
+    launches_step = len(jobs)
+
+    def run_step():
+        for blob, x, y, (n, k) in zip(blobs, xs, ys, dims):
+            ptq.ptqtp_gemv(blob, x, n, k, out=y)
+
+    stream = torch.cuda.Stream()          # default priority
+    graph = None
+    with torch.cuda.stream(stream):
+        run_step()
+        stream.synchronize()
+        if args.mode == "graph":
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                run_step()
+        step = graph.replay if graph is not None else run_step
+
+        for _ in range(args.warmup):
+            step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        wall0 = time.perf_counter()
+        ev0.record(stream)
+        for _ in range(args.steps):
+            step()
+        ev1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - wall0
+        gpu_ms = ev0.elapsed_time(ev1)
+
+    ms_per_step = max(gpu_ms, wall * 1e3) / args.steps
+    gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
+    launch_us = ms_per_step * 1e3 / launches_step
+    bytes_launch = bytes_step / launches_step
+
+    extra = {}
+    if args.per_shape:
+        extra["per_shape"] = per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream)
+
+    out = {
+        "metric": "ternary GEMV effective HBM GB/s, 8B shapes b=1 (one decode step through the stack)",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[1] 8B-shaped decoder linears (q,k,v,o,gate,up,down) at batch 1, group 128, "
+                               f"walked over {args.layers} distinct layer copies (= configs[3] stack)",
+                   "layers": args.layers, "launches_per_step": launches_step, "launch_mode": args.mode,
+                   "bytes_per_step": bytes_step},
+        "us_per_decode_step": round(ms_per_step * 1e3, 2),
+        "pct_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "roofline": {"bound": "hbm", "achieved": round(bytes_launch / (launch_us * 1e-6) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(bytes_launch / (launch_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "gemv_kernel<1,1,true>", "avg_launch_us": round(launch_us, 3),
+                     "bytes_per_launch": round(bytes_launch)},
+    }
+    out.update(extra)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layer0, names)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, reps=200):
+    """Each distinct shape on its own: `cold` walks the 32 layer copies, `hot` re-runs layer 0's blob."""
+    res = {}
+    with torch.cuda.stream(stream):
+        for name in ("q", "k", "gate", "down"):
+            idxs = [i for i, j in enumerate(jobs) if j[1] == name]
+            n, k = dims[idxs[0]]
+            for label, seq in (("cold", idxs), ("hot", idxs[:1])):
+                g = torch.cuda.CUDAGraph()
+                order = [seq[i % len(seq)] for i in range(reps)]
+                for i in order[:4]:
+                    ptq.ptqtp_gemv(blobs[i], xs[i], n, k, out=ys[i])
+                stream.synchronize()
+                with torch.cuda.graph(g, stream=stream):
+                    for i in order:
+                        ptq.ptqtp_gemv(blobs[i], xs[i], n, k, out=ys[i])
+                g.replay()
+                stream.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(5):
+                    g.replay()
+                e1.record(stream)
+                stream.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (5 * reps)
+                res[f"{name}_{n}x{k}_{label}"] = {"us": round(us, 3),
+                                                  "GBps": round(algorithmic_bytes(n, k) / us / 1e3, 1)}
+    return res
+
+
+def cpu_baseline(layer0, names):
+    """The fp64 oracle, as it stands, on the host cores: layer 0's seven linears at batch 1."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    threads = min(16, os.cpu_count() or 1)
+    total_bytes = 0
+    t_total = 0.0
+    reps = 0
+    budget = 15.0
+    t_start = time.perf_counter()
+    while time.perf_counter() - t_start < budget and reps < 3:
+        for name in names:
+            lin = layer0[name]
+            x = workloads.x_for(name, 1, lin["K"], 1, 0)
+            t = time.perf_counter()
+            oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=threads, want_bound=False)
+            t_total += time.perf_counter() - t
+            total_bytes += algorithmic_bytes(lin["N"], lin["K"])
+        reps += 1
+    return {"value": round(total_bytes / t_total / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"layer 0 of the stack (seven 8B-shaped linears, batch 1), {reps} pass(es), "
+                      f"{t_total / reps * 1e3:.0f} ms per layer; same algorithmic bytes as the GPU figure",
+            "us_per_decode_step_extrapolated": round(t_total / reps * 32 * 1e6)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,142 @@
+/*
+ * libptqtp -- the decode-time hot path of PTQTP on AMD MI355X (gfx950).
+ *
+ * The layer (paper, Sec. "Magnitude-Topology Decoupling", Eq. 1-2; scales made
+ * group-wise along the input dimension by paragraph "Batch Processing", G = 128):
+ *
+ *   y[m,n] = sum_g ( alpha1[n,g] * sum_{k in g} T1[n,k] x[m,k]
+ *                  + alpha2[n,g] * sum_{k in g} T2[n,k] x[m,k] )
+ *
+ *   T1, T2 in {-1,0,+1}^{N x K}   two trit planes  (N = out features, K = in features)
+ *   alpha1, alpha2  fp16 [N, K/G] one scale per (output row, group of G inputs)
+ *   x  fp16 [M, K]  activations,  y  [M, N]  (no bias: the decomposition is bias-free)
+ *
+ * Sec. "Inference Efficiency" observes that a product with a trit is a sign
+ * flip, a copy or a zero, so the plane products need additions only and the
+ * two planes are independent; the only true multiplies are the 2 per
+ * (row, group) scale applications.  Storage follows the appendix memory model:
+ * 2 bits per trit per plane + two fp16 scales per (row, group) = 4 + 32/G bits
+ * per weight (4.25 at G = 128).
+ *
+ * Conventions for every entry point
+ *   - Pointers named "device" are HIP device pointers, 16-byte aligned (the packed
+ *     blob and workspace 256-byte aligned); the caller owns every buffer.  The
+ *     library never allocates, frees or synchronises: work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = default stream) and runs
+ *     asynchronously.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     non-zero status means nothing was enqueued and no memory was touched.
+ *   - Outputs are overwritten, never accumulated into.  Results are
+ *     deterministic: no atomics on floating-point data, fixed reduction order.
+ *   - `group` must be 128.  K must be a multiple of `group`.  N is arbitrary
+ *     (rows are padded to a multiple of 16 inside the blob; padding is never
+ *     written to y).
+ */
+#ifndef PTQTP_H
+#define PTQTP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t ptqtp_status;
+enum {
+    PTQTP_OK         = 0,
+    PTQTP_ERR_NULL   = 1,  /* a required pointer is NULL                                   */
+    PTQTP_ERR_SHAPE  = 2,  /* M, N or K not positive, K % group != 0, M out of range       */
+    PTQTP_ERR_GROUP  = 3,  /* group size not supported (only 128)                          */
+    PTQTP_ERR_SIZE   = 4,  /* packed_bytes / workspace_bytes smaller than required         */
+    PTQTP_ERR_DTYPE  = 5,  /* y_dtype is neither PTQTP_F32 nor PTQTP_F16                   */
+    PTQTP_ERR_ALIGN  = 6,  /* a device pointer is not aligned as required                  */
+    PTQTP_ERR_HIP    = 7   /* the HIP runtime reported an error at launch                  */
+};
+
+enum { PTQTP_F32 = 0, PTQTP_F16 = 1 };   /* y_dtype */
+
+/* Largest batch ptqtp_gemm_small accepts on its streamed path. */
+#define PTQTP_GEMM_SMALL_MAX_M 64
+
+/* Library version: major*10000 + minor*100 + patch. */
+int32_t ptqtp_version(void);
+
+/* Static string for a status code (never NULL). */
+const char *ptqtp_status_string(ptqtp_status s);
+
+/*
+ * Size in bytes of the packed blob for an N x K layer (appendix memory model:
+ * N*K/2 bytes of planes + 4*N*K/group bytes of scales, after padding N to a
+ * multiple of 16 and K to a multiple of 256, plus a 256-byte header).
+ * Returns 0 for invalid arguments.  `M` is a batch hint and is currently ignored.
+ */
+size_t ptqtp_packed_bytes(int64_t M, int64_t N, int64_t K, int32_t group);
+
+/* Workspace the compute calls need for this shape (currently always 0: the
+ * cross-wave reduction lives in LDS).  Returns 0 for invalid arguments too. */
+size_t ptqtp_workspace_bytes(int64_t M, int64_t N, int64_t K, int32_t group);
+
+/*
+ * Pack two trit planes and their scales into the device layout the compute
+ * kernels stream (appendix memory model: 2-bit trits, fp16 scales).
+ *
+ *   T1, T2      device, int8 [N, K] row-major, entries in {-1,0,+1}
+ *   a1, a2      device, fp16 bit patterns [N, K/group] row-major
+ *   packed      device, receives ptqtp_packed_bytes(M,N,K,group) bytes; opaque
+ *   dev_status  device int32 or NULL; set to 0, then to 1 by the kernel if any
+ *               entry of T1/T2 lies outside {-1,0,+1} (such an entry is stored as 0)
+ * One-time, stream-ordered; not part of the timed decode step.
+ */
+ptqtp_status ptqtp_pack(const int8_t *T1, const int8_t *T2,
+                        const uint16_t *a1, const uint16_t *a2,
+                        int64_t M, int64_t N, int64_t K, int32_t group,
+                        void *packed, size_t packed_bytes,
+                        int32_t *dev_status, void *stream);
+
+/*
+ * Inverse of ptqtp_pack (bit-exact): recovers T1, T2 (int8 [N,K]) and a1, a2
+ * (fp16 bits [N,K/group]) from a blob.  All pointers device.  Any of the four
+ * outputs may be NULL to skip it.
+ */
+ptqtp_status ptqtp_unpack(const void *packed, int64_t M, int64_t N, int64_t K, int32_t group,
+                          int8_t *T1, int8_t *T2, uint16_t *a1, uint16_t *a2, void *stream);
+
+/*
+ * Batch-1 forward of the dual trit-plane layer (Eq. 1-2, group-wise scales):
+ *   y[n] = sum_g alpha1[n,g]*(T1[n,g,:] . x[g,:]) + alpha2[n,g]*(T2[n,g,:] . x[g,:])
+ *
+ *   packed   device, blob from ptqtp_pack for the same N, K, group
+ *   x        device, fp16 bits [K]
+ *   y        device, [N] of float (PTQTP_F32) or fp16 bits (PTQTP_F16)
+ *   M        must be 1
+ *   workspace, workspace_bytes   device scratch of >= ptqtp_workspace_bytes(...)
+ *            bytes; may be NULL when that is 0
+ * fp32 accumulation of exact +-x terms; one fp32 multiply per (row, group, plane).
+ */
+ptqtp_status ptqtp_gemv(const void *packed, const uint16_t *x, void *y, int32_t y_dtype,
+                        int64_t M, int64_t N, int64_t K, int32_t group,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Small-batch forward, 1 <= M <= PTQTP_GEMM_SMALL_MAX_M: the same sum for every
+ * token m, each decoded trit reused for all M tokens.
+ *   x  device fp16 bits [M, K] row-major;  y  device [M, N] row-major.
+ */
+ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, int32_t y_dtype,
+                              int64_t M, int64_t N, int64_t K, int32_t group,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tuning hook for benchmarks and sweeps (not needed for correct use): override
+ * the launch shape the compute calls pick.  key = "gemv_waves" (waves per
+ * workgroup, 1..16), "gemv_rows" (16-row tiles per workgroup, 1, 2 or 4);
+ * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
+ * unknown key or out-of-range value.  Not thread-safe.
+ */
+ptqtp_status ptqtp_tune(const char *key, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PTQTP_H */

@@ -1,0 +1,152 @@
+"""ctypes binding with the same names as include/ptqtp.h.
+
+Tensors are torch CUDA(HIP) tensors; the binding only checks dtype/device/
+contiguity, allocates outputs, and passes raw pointers plus the current stream.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+PTQTP_F32, PTQTP_F16 = 0, 1
+PTQTP_GEMM_SMALL_MAX_M = 64
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libptqtp.so")
+_lib = None
+
+
+class PtqtpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where}: {ptqtp_status_string(status)} (status {status})")
+        self.status = status
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        p, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+        lib.ptqtp_version.restype = i32
+        lib.ptqtp_version.argtypes = []
+        lib.ptqtp_status_string.restype = ctypes.c_char_p
+        lib.ptqtp_status_string.argtypes = [i32]
+        lib.ptqtp_packed_bytes.restype = sz
+        lib.ptqtp_packed_bytes.argtypes = [i64, i64, i64, i32]
+        lib.ptqtp_workspace_bytes.restype = sz
+        lib.ptqtp_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        lib.ptqtp_pack.restype = i32
+        lib.ptqtp_pack.argtypes = [p, p, p, p, i64, i64, i64, i32, p, sz, p, p]
+        lib.ptqtp_unpack.restype = i32
+        lib.ptqtp_unpack.argtypes = [p, i64, i64, i64, i32, p, p, p, p, p]
+        lib.ptqtp_gemv.restype = i32
+        lib.ptqtp_gemv.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
+        lib.ptqtp_gemm_small.restype = i32
+        lib.ptqtp_gemm_small.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
+        lib.ptqtp_tune.restype = i32
+        lib.ptqtp_tune.argtypes = [ctypes.c_char_p, i32]
+        _lib = lib
+    return _lib
+
+
+def raw():
+    """The ctypes library handle (for tests of the C ABI itself)."""
+    return _load()
+
+
+def ptqtp_version() -> int:
+    return int(_load().ptqtp_version())
+
+
+def ptqtp_status_string(status: int) -> str:
+    return _load().ptqtp_status_string(int(status)).decode()
+
+
+def ptqtp_packed_bytes(M: int, N: int, K: int, group: int = 128) -> int:
+    return int(_load().ptqtp_packed_bytes(M, N, K, group))
+
+
+def ptqtp_workspace_bytes(M: int, N: int, K: int, group: int = 128) -> int:
+    return int(_load().ptqtp_workspace_bytes(M, N, K, group))
+
+
+def ptqtp_tune(key: str, value: int) -> None:
+    st = _load().ptqtp_tune(key.encode(), int(value))
+    if st:
+        raise PtqtpError(st, "ptqtp_tune")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU, got {t.dtype} on {t.device}")
+    return t.data_ptr()
+
+
+def ptqtp_pack(T1, T2, a1, a2, M: int = 1, group: int = 128, check: bool = True) -> torch.Tensor:
+    """Pack int8 planes [N,K] and fp16 scales [N,K/group] -> opaque uint8 blob on the GPU."""
+    N, K = T1.shape
+    nbytes = ptqtp_packed_bytes(M, N, K, group)
+    if nbytes == 0:
+        raise PtqtpError(2 if group == 128 else 3, "ptqtp_packed_bytes")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=T1.device)
+    status = torch.empty(1, dtype=torch.int32, device=T1.device)
+    st = _load().ptqtp_pack(_dev(T1, torch.int8, "T1"), _dev(T2, torch.int8, "T2"),
+                            _dev(a1, torch.float16, "a1"), _dev(a2, torch.float16, "a2"),
+                            M, N, K, group, packed.data_ptr(), nbytes, status.data_ptr(), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_pack")
+    if check and int(status.item()) != 0:
+        raise ValueError("ptqtp_pack: a plane holds a value outside {-1, 0, +1}")
+    return packed
+
+
+def ptqtp_unpack(packed: torch.Tensor, N: int, K: int, M: int = 1, group: int = 128):
+    dev = packed.device
+    T1 = torch.empty((N, K), dtype=torch.int8, device=dev)
+    T2 = torch.empty((N, K), dtype=torch.int8, device=dev)
+    a1 = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+    a2 = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+    st = _load().ptqtp_unpack(_dev(packed, torch.uint8, "packed"), M, N, K, group, T1.data_ptr(), T2.data_ptr(),
+                              a1.data_ptr(), a2.data_ptr(), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_unpack")
+    return T1, T2, a1, a2
+
+
+def _forward(fn, where, packed, x, N, K, M, group, y_dtype, out):
+    ydt = torch.float32 if y_dtype == PTQTP_F32 else torch.float16
+    if out is None:
+        out = torch.empty((M, N), dtype=ydt, device=x.device)
+    st = fn(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"), _dev(out, ydt, "y"), y_dtype,
+            M, N, K, group, None, 0, _stream())
+    if st:
+        raise PtqtpError(st, where)
+    return out
+
+
+def ptqtp_gemv(packed, x, N: int, K: int, group: int = 128, y_dtype: int = PTQTP_F32, out=None):
+    """y [1,N] = dual trit-plane layer applied to x (fp16, K elements)."""
+    if x.numel() != K:
+        raise PtqtpError(2, "ptqtp_gemv")
+    return _forward(_load().ptqtp_gemv, "ptqtp_gemv", packed, x, N, K, 1, group, y_dtype, out)
+
+
+def ptqtp_gemm_small(packed, x, N: int, K: int, group: int = 128, y_dtype: int = PTQTP_F32, out=None):
+    """y [M,N] for x fp16 [M,K], 1 <= M <= 64."""
+    if x.dim() != 2 or x.shape[1] != K:
+        raise PtqtpError(2, "ptqtp_gemm_small")
+    return _forward(_load().ptqtp_gemm_small, "ptqtp_gemm_small", packed, x, N, K, x.shape[0], group, y_dtype, out)

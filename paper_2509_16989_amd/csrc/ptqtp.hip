@@ -1,0 +1,483 @@
+// libptqtp: dual trit-plane linear layer for MI355X (gfx950, wave64, MFMA).
+//
+// y[m,n] = sum_g alpha1[n,g] * (T1[n,g,:] . x[m,g,:]) + alpha2[n,g] * (T2[n,g,:] . x[m,g,:])
+// (paper, Eq. 1-2 with the group-wise scales of paragraph "Batch Processing").
+//
+// Device layout of the packed blob (layout id 1)
+// ----------------------------------------------
+//   [ 256-byte header ][ record(rt=0,ks=0) ][ record(rt=0,ks=1) ] ... [ record(rt=RT-1,ks=KS-1) ]
+//   rt = 16-row tile (RT = ceil(N/16)), ks = 256-column step (KS = ceil(K/256)) = two scale groups.
+//   One record = 2176 bytes = 17 cache lines of 128 B:
+//     bytes    0..1023  plane 1, 64 lanes x 16 B   (one global_load_dwordx4 per wave)
+//     bytes 1024..2047  plane 2, same shape
+//     bytes 2048..2175  scales: row nl (0..15) -> {a1[g0], a1[g1], a2[g0], a2[g1]} fp16
+//   Lane l = q*16 + nl holds 64 trits of row rt*16+nl: word i (0..3), 16-bit half h (0..1),
+//   2-bit field f (0..7) is column
+//       k = ks*256 + (f/4)*128 + q*32 + (f%4)*8 + i*2 + h
+//   and sits at bits [16h+15-2f : 16h+14-2f] as (sign, nonzero): 0 -> 00, +1 -> 01, -1 -> 11.
+//   Decoding field f of all four words is `(w << 2f) & 0xC000C000`: the two halves become the
+//   fp16 values {0, +2.0, -2.0}; the eight halves of a lane are exactly one lane's share of the
+//   32-deep K dimension of v_mfma_f32_16x16x32_f16.  Fields 0..3 belong to scale group g0 and
+//   4..7 to g1, so four MFMAs accumulate one (row, group) trit sum for 16 rows x 16 tokens.
+//
+// Why MFMA for a GEMV: "multiplication-free" (Sec. "Inference Efficiency") is a statement about
+// the mathematics.  On CDNA4 a product by +-2.0/0 in the matrix pipe is exact and is the cheapest
+// way to add: it leaves the vector ALU only the 1 shift + 1 and per trit pair, which is what
+// keeps the kernel under the HBM roof instead of the VALU roof.  The factor 2 is removed exactly
+// by a final multiply with 0.5.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "ptqtp.h"
+
+namespace {
+
+constexpr int kHeaderBytes = 256;
+constexpr int kTileRows = 16;
+constexpr int kStepK = 256;
+constexpr int kPlaneBytes = 1024;
+constexpr int kRecordBytes = 2 * kPlaneBytes + 128;
+constexpr uint64_t kMagic = 0x3130765054515450ull;  // "PTQTPv01" little-endian
+constexpr uint32_t kLayoutId = 1;
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+
+struct BlobHeader {
+    uint64_t magic;
+    uint32_t layout;
+    int32_t group;
+    int64_t N, K, RT, KS;
+};
+
+struct Shape {
+    int64_t N, K, RT, KS, NG;
+};
+
+inline bool make_shape(int64_t M, int64_t N, int64_t K, int32_t group, Shape *s, ptqtp_status *st) {
+    if (group != 128) { *st = PTQTP_ERR_GROUP; return false; }
+    if (M <= 0 || N <= 0 || K <= 0 || K % group != 0 || N > (1ll << 30) || K > (1ll << 30)) {
+        *st = PTQTP_ERR_SHAPE; return false;
+    }
+    s->N = N; s->K = K; s->NG = K / group;
+    s->RT = (N + kTileRows - 1) / kTileRows;
+    s->KS = (K + kStepK - 1) / kStepK;
+    *st = PTQTP_OK;
+    return true;
+}
+
+inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// ------------------------------------------------------------------------------------------
+// pack / unpack
+// ------------------------------------------------------------------------------------------
+__global__ void clear_status_kernel(int32_t *st) { *st = 0; }
+
+// One workgroup per record; threads 0..511 build one 32-bit plane word each, 512..575 one scale.
+__global__ void __launch_bounds__(576)
+pack_kernel(const int8_t *__restrict__ T1, const int8_t *__restrict__ T2,
+            const uint16_t *__restrict__ a1, const uint16_t *__restrict__ a2,
+            uint8_t *__restrict__ blob, int64_t N, int64_t K, int64_t RT, int64_t KS, int64_t NG,
+            int32_t *__restrict__ dev_status)
+{
+    const int64_t recno = blockIdx.x;
+    const int64_t rt = recno / KS, ks = recno % KS;
+    uint8_t *rec = blob + kHeaderBytes + recno * kRecordBytes;
+    const int t = threadIdx.x;
+    if (recno == 0 && t == 0) {
+        BlobHeader h;
+        h.magic = kMagic; h.layout = kLayoutId; h.group = 128; h.N = N; h.K = K; h.RT = RT; h.KS = KS;
+        *reinterpret_cast<BlobHeader *>(blob) = h;
+    }
+    if (recno == 0 && t >= 12 && t < 64) reinterpret_cast<uint32_t *>(blob)[t] = 0;  // header tail (48..255)
+    if (t < 512) {
+        const int plane = t >> 8, lane = (t >> 2) & 63, i = t & 3;
+        const int nl = lane & 15, q = lane >> 4;
+        const int64_t n = rt * kTileRows + nl;
+        const int8_t *T = plane ? T2 : T1;
+        uint32_t word = 0;
+        bool bad = false;
+        if (n < N) {
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+                const int64_t k = ks * kStepK + (f >> 2) * 128 + q * 32 + (f & 3) * 8 + i * 2;
+                if (k < K) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        int v = T[n * K + k + h];
+                        if (v < -1 || v > 1) { bad = true; v = 0; }
+                        word |= (static_cast<uint32_t>(v) & 3u) << (16 * h + 14 - 2 * f);
+                    }
+                }
+            }
+        }
+        reinterpret_cast<uint32_t *>(rec)[t] = word;
+        if (bad && dev_status) atomicOr(dev_status, 1);
+    } else {
+        const int e = t - 512;           // 0..63: row nl = e/4, slot j = e%4
+        const int nl = e >> 2, j = e & 3;
+        const int64_t n = rt * kTileRows + nl;
+        const int64_t g = ks * 2 + (j & 1);
+        uint16_t v = 0;
+        if (n < N && g < NG) v = (j >> 1) ? a2[n * NG + g] : a1[n * NG + g];
+        reinterpret_cast<uint16_t *>(rec + 2 * kPlaneBytes)[e] = v;
+    }
+}
+
+// One thread per (n, k): pulls the trit of both planes back out of its record.
+__global__ void __launch_bounds__(256)
+unpack_trits_kernel(const uint8_t *__restrict__ blob, int8_t *__restrict__ T1, int8_t *__restrict__ T2,
+                    int64_t N, int64_t K, int64_t KS)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= N * K) return;
+    const int64_t n = idx / K, k = idx % K;
+    const int64_t rt = n / kTileRows, ks = k / kStepK;
+    const int nl = static_cast<int>(n % kTileRows);
+    const int kk = static_cast<int>(k % kStepK);
+    const int g2 = kk >> 7, q = (kk >> 5) & 3, fm = (kk >> 3) & 3, i = (kk >> 1) & 3, h = kk & 1;
+    const int f = g2 * 4 + fm, lane = q * 16 + nl;
+    const uint8_t *rec = blob + kHeaderBytes + (rt * KS + ks) * kRecordBytes;
+#pragma unroll
+    for (int plane = 0; plane < 2; ++plane) {
+        int8_t *T = plane ? T2 : T1;
+        if (!T) continue;
+        const uint32_t w = reinterpret_cast<const uint32_t *>(rec + plane * kPlaneBytes)[lane * 4 + i];
+        const uint32_t code = (w >> (16 * h + 14 - 2 * f)) & 3u;
+        T[idx] = static_cast<int8_t>(code == 3u ? -1 : static_cast<int>(code & 1u));
+    }
+}
+
+__global__ void __launch_bounds__(256)
+unpack_scales_kernel(const uint8_t *__restrict__ blob, uint16_t *__restrict__ a1, uint16_t *__restrict__ a2,
+                     int64_t N, int64_t NG, int64_t KS)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= N * NG) return;
+    const int64_t n = idx / NG, g = idx % NG;
+    const int64_t rt = n / kTileRows, ks = g / 2;
+    const int nl = static_cast<int>(n % kTileRows), j = static_cast<int>(g & 1);
+    const uint16_t *sc = reinterpret_cast<const uint16_t *>(
+        blob + kHeaderBytes + (rt * KS + ks) * kRecordBytes + 2 * kPlaneBytes);
+    if (a1) a1[idx] = sc[nl * 4 + j];
+    if (a2) a2[idx] = sc[nl * 4 + 2 + j];
+}
+
+// ------------------------------------------------------------------------------------------
+// streamed GEMV / small-batch GEMM on the matrix pipe
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float half_bits_to_float(uint32_t bits16) {
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(bits16)));
+}
+
+// Field f of four packed words -> eight fp16 values in {0, +2, -2}: one lane's MFMA B operand.
+template <int F>
+__device__ __forceinline__ half8 decode_field(uintx4 w) {
+    uintx4 b;
+    b.x = (w.x << (2 * F)) & 0xC000C000u;
+    b.y = (w.y << (2 * F)) & 0xC000C000u;
+    b.z = (w.z << (2 * F)) & 0xC000C000u;
+    b.w = (w.w << (2 * F)) & 0xC000C000u;
+    return __builtin_bit_cast(half8, b);
+}
+
+// One (plane, 128-column group): four MFMAs of 16 tokens x 16 rows x 32 columns each.
+template <int MT, int G2>
+__device__ __forceinline__ void group_sum(const uintx4 (&xa)[MT][8], uintx4 p, floatx4 (&acc)[MT]) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    half8 b;
+    b = decode_field<G2 * 4 + 0>(p);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[mt][G2 * 4 + 0]), b, acc[mt], 0, 0, 0);
+    b = decode_field<G2 * 4 + 1>(p);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[mt][G2 * 4 + 1]), b, acc[mt], 0, 0, 0);
+    b = decode_field<G2 * 4 + 2>(p);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[mt][G2 * 4 + 2]), b, acc[mt], 0, 0, 0);
+    b = decode_field<G2 * 4 + 3>(p);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[mt][G2 * 4 + 3]), b, acc[mt], 0, 0, 0);
+}
+
+// Workgroup = W waves sharing R consecutive 16-row tiles; wave w takes the 256-column steps
+// ks = w, w+W, ...  Lane l = q*16 + nl: as MFMA A operand it carries token (mt*16 + nl), as B
+// operand row (rt*16 + nl), both for the same 8 columns per MFMA; the result D has token
+// 4q+j (j = 0..3) of row nl in register j.  SINGLE is the batch-1 path: only token 0 is
+// loaded and only register 0 of lanes 0..15 is kept.
+template <int MT, int R, bool SINGLE>
+__global__ void __launch_bounds__(MT == 1 ? 1024 : 512)
+gemv_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
+            int M, int N, int K, int RT, int KS, int y_f16)
+{
+    extern __shared__ float red[];
+    constexpr int MR = SINGLE ? 1 : 4;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, W = blockDim.x >> 6;
+    const int nl = lane & 15, q = lane >> 4;
+    const int rt0 = blockIdx.x * R;
+
+    float yacc[R][MT][MR];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < MR; ++j) yacc[r][mt][j] = 0.f;
+
+    for (int ks = w; ks < KS; ks += W) {
+        // weights first: they come from HBM and have the longest latency
+        uintx4 p1[R], p2[R];
+        uintx2 sc[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int rt = rt0 + r;
+            if (rt < RT) {
+                const uint8_t *rec = records + (static_cast<size_t>(rt) * KS + ks) * kRecordBytes;
+                p1[r] = *reinterpret_cast<const uintx4 *>(rec + lane * 16);
+                p2[r] = *reinterpret_cast<const uintx4 *>(rec + kPlaneBytes + lane * 16);
+                sc[r] = *reinterpret_cast<const uintx2 *>(rec + 2 * kPlaneBytes + nl * 8);
+            } else {
+                p1[r] = uintx4{0, 0, 0, 0}; p2[r] = uintx4{0, 0, 0, 0}; sc[r] = uintx2{0, 0};
+            }
+        }
+        // activations for this step (L2-resident): lane (token nl, quarter q), 8 columns per field
+        uintx4 xa[MT][8];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = mt * 16 + nl;
+            const bool live = SINGLE ? (nl == 0) : (m < M);
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+                const int k0 = ks * kStepK + (f >> 2) * 128 + q * 32 + (f & 3) * 8;
+                xa[mt][f] = uintx4{0, 0, 0, 0};
+                if (live && k0 < K)
+                    xa[mt][f] = *reinterpret_cast<const uintx4 *>(x + static_cast<size_t>(m) * K + k0);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float a1g0 = half_bits_to_float(sc[r].x & 0xffffu), a1g1 = half_bits_to_float(sc[r].x >> 16);
+            const float a2g0 = half_bits_to_float(sc[r].y & 0xffffu), a2g1 = half_bits_to_float(sc[r].y >> 16);
+            floatx4 acc[MT];
+            group_sum<MT, 0>(xa, p1[r], acc);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < MR; ++j) yacc[r][mt][j] = fmaf(a1g0, acc[mt][j], yacc[r][mt][j]);
+            group_sum<MT, 1>(xa, p1[r], acc);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < MR; ++j) yacc[r][mt][j] = fmaf(a1g1, acc[mt][j], yacc[r][mt][j]);
+            group_sum<MT, 0>(xa, p2[r], acc);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < MR; ++j) yacc[r][mt][j] = fmaf(a2g0, acc[mt][j], yacc[r][mt][j]);
+            group_sum<MT, 1>(xa, p2[r], acc);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < MR; ++j) yacc[r][mt][j] = fmaf(a2g1, acc[mt][j], yacc[r][mt][j]);
+        }
+    }
+
+    // cross-wave reduction in LDS, fixed order => bit-identical run to run
+    constexpr int OUT = SINGLE ? R * 16 : R * MT * 256;   // partials per wave
+    if (SINGLE) {
+        if (q == 0) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) red[w * OUT + r * 16 + nl] = yacc[r][0][0];
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    red[w * OUT + ((r * MT + mt) * 16 + 4 * q + j) * 16 + nl] = yacc[r][mt][j];
+    }
+    __syncthreads();
+    for (int o = threadIdx.x; o < OUT; o += blockDim.x) {
+        float s = 0.f;
+        for (int ww = 0; ww < W; ++ww) s += red[ww * OUT + o];
+        s *= 0.5f;   // trits were decoded as +-2.0
+        int r, m;
+        const int on = o & 15;
+        if (SINGLE) { r = o >> 4; m = 0; }
+        else { const int t = o >> 4; m = (t / 16 % MT) * 16 + (t & 15); r = t / (16 * MT); }
+        const int n = (rt0 + r) * kTileRows + on;
+        if (m < M && n < N) {
+            const size_t off = static_cast<size_t>(m) * N + n;
+            if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(s);
+            else reinterpret_cast<float *>(y)[off] = s;
+        }
+    }
+}
+
+int g_tune_waves = 0, g_tune_rows = 0;
+
+template <int MT, int R, bool SINGLE>
+hipError_t launch_gemv(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s,
+                       int W, int y_f16, hipStream_t stream)
+{
+    const int grid = static_cast<int>((s.RT + R - 1) / R);
+    const size_t lds = static_cast<size_t>(W) * (SINGLE ? R * 16 : R * MT * 256) * sizeof(float);
+    hipLaunchKernelGGL((gemv_kernel<MT, R, SINGLE>), dim3(grid), dim3(W * 64), lds, stream, records, x, y, M,
+                       static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
+                       static_cast<int>(s.KS), y_f16);
+    return hipGetLastError();
+}
+
+// Waves per workgroup: the fewest waves that reach the minimal number of steps per wave.
+int pick_waves(int64_t KS, int wmax) {
+    if (g_tune_waves > 0) return g_tune_waves < wmax ? g_tune_waves : wmax;
+    const int64_t per = (KS + wmax - 1) / wmax;
+    int W = static_cast<int>((KS + per - 1) / per);
+    return W < 1 ? 1 : W;
+}
+
+ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M,
+                         int64_t N, int64_t K, int32_t group, void *stream_)
+{
+    Shape s;
+    ptqtp_status st;
+    if (!packed || !x || !y) return PTQTP_ERR_NULL;
+    if (!make_shape(M, N, K, group, &s, &st)) return st;
+    if (M > PTQTP_GEMM_SMALL_MAX_M) return PTQTP_ERR_SHAPE;
+    if (y_dtype != PTQTP_F32 && y_dtype != PTQTP_F16) return PTQTP_ERR_DTYPE;
+    if (!aligned(packed, 256) || !aligned(x, 16) || !aligned(y, y_dtype == PTQTP_F16 ? 2 : 4)) return PTQTP_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const uint8_t *records = static_cast<const uint8_t *>(packed) + kHeaderBytes;
+    const int Mi = static_cast<int>(M), f16 = (y_dtype == PTQTP_F16);
+    hipError_t e;
+    if (M == 1) {
+        const int W = pick_waves(s.KS, 16);
+        int R = g_tune_rows > 0 ? g_tune_rows : (s.RT >= 4096 ? 2 : 1);
+        if (R >= 4) e = launch_gemv<1, 4, true>(records, x, y, Mi, s, W, f16, stream);
+        else if (R >= 2) e = launch_gemv<1, 2, true>(records, x, y, Mi, s, W, f16, stream);
+        else e = launch_gemv<1, 1, true>(records, x, y, Mi, s, W, f16, stream);
+    } else if (M <= 16) {
+        const int W = pick_waves(s.KS, 16);
+        int R = g_tune_rows > 0 ? g_tune_rows : (s.RT >= 4096 ? 2 : 1);
+        if (R >= 4) e = launch_gemv<1, 4, false>(records, x, y, Mi, s, W, f16, stream);
+        else if (R >= 2) e = launch_gemv<1, 2, false>(records, x, y, Mi, s, W, f16, stream);
+        else e = launch_gemv<1, 1, false>(records, x, y, Mi, s, W, f16, stream);
+    } else if (M <= 32) {
+        const int W = pick_waves(s.KS, 8);
+        e = launch_gemv<2, 1, false>(records, x, y, Mi, s, W, f16, stream);
+    } else {
+        const int W = pick_waves(s.KS, 8);
+        e = launch_gemv<4, 1, false>(records, x, y, Mi, s, W, f16, stream);
+    }
+    return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ptqtp_version(void) { return 100; }
+
+const char *ptqtp_status_string(ptqtp_status s) {
+    switch (s) {
+        case PTQTP_OK: return "ok";
+        case PTQTP_ERR_NULL: return "null pointer";
+        case PTQTP_ERR_SHAPE: return "invalid shape";
+        case PTQTP_ERR_GROUP: return "unsupported group size";
+        case PTQTP_ERR_SIZE: return "buffer too small";
+        case PTQTP_ERR_DTYPE: return "unsupported output dtype";
+        case PTQTP_ERR_ALIGN: return "misaligned pointer";
+        case PTQTP_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+size_t ptqtp_packed_bytes(int64_t M, int64_t N, int64_t K, int32_t group) {
+    Shape s;
+    ptqtp_status st;
+    if (!make_shape(M, N, K, group, &s, &st)) return 0;
+    return static_cast<size_t>(kHeaderBytes) + static_cast<size_t>(s.RT) * s.KS * kRecordBytes;
+}
+
+size_t ptqtp_workspace_bytes(int64_t, int64_t, int64_t, int32_t) { return 0; }
+
+ptqtp_status ptqtp_pack(const int8_t *T1, const int8_t *T2, const uint16_t *a1, const uint16_t *a2,
+                        int64_t M, int64_t N, int64_t K, int32_t group, void *packed, size_t packed_bytes,
+                        int32_t *dev_status, void *stream_)
+{
+    Shape s;
+    ptqtp_status st;
+    if (!T1 || !T2 || !a1 || !a2 || !packed) return PTQTP_ERR_NULL;
+    if (!make_shape(M, N, K, group, &s, &st)) return st;
+    if (packed_bytes < ptqtp_packed_bytes(M, N, K, group)) return PTQTP_ERR_SIZE;
+    if (!aligned(packed, 256) || !aligned(T1, 2) || !aligned(T2, 2) || !aligned(a1, 2) || !aligned(a2, 2))
+        return PTQTP_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (dev_status) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, stream, dev_status);
+    hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(s.RT * s.KS)), dim3(576), 0, stream, T1, T2, a1, a2,
+                       static_cast<uint8_t *>(packed), s.N, s.K, s.RT, s.KS, s.NG, dev_status);
+    return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
+ptqtp_status ptqtp_unpack(const void *packed, int64_t M, int64_t N, int64_t K, int32_t group, int8_t *T1,
+                          int8_t *T2, uint16_t *a1, uint16_t *a2, void *stream_)
+{
+    Shape s;
+    ptqtp_status st;
+    if (!packed) return PTQTP_ERR_NULL;
+    if (!make_shape(M, N, K, group, &s, &st)) return st;
+    if (!aligned(packed, 256)) return PTQTP_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const uint8_t *blob = static_cast<const uint8_t *>(packed);
+    if (T1 || T2) {
+        const int64_t blocks = (s.N * s.K + 255) / 256;
+        hipLaunchKernelGGL(unpack_trits_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, blob, T1,
+                           T2, s.N, s.K, s.KS);
+    }
+    if (a1 || a2) {
+        const int64_t blocks = (s.N * s.NG + 255) / 256;
+        hipLaunchKernelGGL(unpack_scales_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, blob, a1,
+                           a2, s.N, s.NG, s.KS);
+    }
+    return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
+ptqtp_status ptqtp_gemv(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M, int64_t N,
+                        int64_t K, int32_t group, void *, size_t, void *stream)
+{
+    if (M != 1) return PTQTP_ERR_SHAPE;
+    return run_forward(packed, x, y, y_dtype, M, N, K, group, stream);
+}
+
+ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M, int64_t N,
+                              int64_t K, int32_t group, void *, size_t, void *stream)
+{
+    return run_forward(packed, x, y, y_dtype, M, N, K, group, stream);
+}
+
+ptqtp_status ptqtp_tune(const char *key, int32_t value) {
+    if (!key) return PTQTP_ERR_NULL;
+    if (!strcmp(key, "gemv_waves")) {
+        if (value < 0 || value > 16) return PTQTP_ERR_SHAPE;
+        g_tune_waves = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "gemv_rows")) {
+        if (value != 0 && value != 1 && value != 2 && value != 4) return PTQTP_ERR_SHAPE;
+        g_tune_rows = value;
+        return PTQTP_OK;
+    }
+    return PTQTP_ERR_SHAPE;
+}
+
+}  // extern "C"

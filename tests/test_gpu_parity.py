@@ -1,0 +1,303 @@
+"""GPU parity: HIP path (through the C ABI) vs the fp64 CPU oracle, element by element.
+
+Bars: packing / indexing bit-exact; floating point |y_gpu - y_oracle| <= 2e-3 * B[m,n]
+with B the per-output L1 bound  sum_k (|a1 T1| + |a2 T2|) |x_k|.  A tighter regression
+gate (1e-5 * B for fp32 output) catches indexing mistakes the loose bar would hide:
+fp32 accumulation of <= 28672 exact terms plus one rounding per scale application
+stays below ~K * 2^-24 * B in the worst case and ~1e-6 * B in practice.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+TIGHT = 1e-5
+TIGHT_F16 = 2.0 ** -10      # one extra rounding to fp16: <= 2^-11 |y| <= 2^-11 B
+
+
+@pytest.fixture(scope="module")
+def ptq():
+    import paper_2509_16989_amd as p
+    return p
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def pack(ptq, lin):
+    return ptq.ptqtp_pack(dev(lin["T1"]), dev(lin["T2"]), dev(lin["a1"]), dev(lin["a2"]))
+
+
+def check(y_gpu, lin, x, tight=TIGHT):
+    y_ref, B = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+    y = y_gpu.detach().cpu().numpy().astype(np.float64)
+    assert y.shape == y_ref.shape
+    err = np.abs(y - y_ref)
+    assert np.all(np.isfinite(y))
+    assert np.all(err <= TOL * B), f"max err/B = {(err / np.maximum(B, 1e-300)).max():.3e}"
+    assert np.all(err <= tight * B), f"regression gate: max err/B = {(err / np.maximum(B, 1e-300)).max():.3e}"
+    assert np.all(y[B == 0] == 0)
+    return float((err / np.maximum(B, 1e-300)).max())
+
+
+# ---------------------------------------------------------------- packing: bit-exact
+@pytest.mark.parametrize("N,K", [(16, 128), (16, 256), (48, 384), (1000, 1024), (1024, 1024), (7, 640), (257, 4096)])
+def test_pack_unpack_roundtrip(ptq, N, K):
+    lin = workloads.make_linear(N, K, 50, N, K)
+    # any finite fp16 scale pattern must survive, including negative, zero, subnormal
+    lin["a1"][0, 0] = np.float16(-1.5)
+    lin["a2"][-1, -1] = np.float16(6e-8)
+    lin["a1"][N // 2, 0] = np.float16(0.0)
+    packed = pack(ptq, lin)
+    assert packed.numel() == ptq.ptqtp_packed_bytes(1, N, K)
+    T1, T2, a1, a2 = ptq.ptqtp_unpack(packed, N, K)
+    assert np.array_equal(T1.cpu().numpy(), lin["T1"])
+    assert np.array_equal(T2.cpu().numpy(), lin["T2"])
+    assert np.array_equal(a1.cpu().numpy().view(np.uint16), lin["a1"].view(np.uint16))
+    assert np.array_equal(a2.cpu().numpy().view(np.uint16), lin["a2"].view(np.uint16))
+
+
+def test_pack_payload_matches_memory_model(ptq):
+    # appendix memory model: 4.25 bits per weight at G = 128
+    for N, K in [(1024, 1024), (4096, 4096), (4096, 14336)]:
+        assert (ptq.ptqtp_packed_bytes(1, N, K) - 256) * 8 == oracle.model_bits(N, K, 128)
+
+
+def test_pack_agrees_with_canonical_storage(ptq):
+    # unpacking the device blob and packing canonically on the host gives the oracle's bytes
+    lin = workloads.make_linear(64, 512, 51)
+    T1, T2, _, _ = ptq.ptqtp_unpack(pack(ptq, lin), 64, 512)
+    assert np.array_equal(oracle.pack_canonical(T1.cpu().numpy()), oracle.pack_canonical(lin["T1"]))
+    assert np.array_equal(oracle.pack_canonical(T2.cpu().numpy()), oracle.pack_canonical(lin["T2"]))
+
+
+def test_pack_flags_bad_trit(ptq):
+    lin = workloads.make_linear(32, 256, 52)
+    lin["T2"][5, 77] = 2
+    with pytest.raises(ValueError):
+        pack(ptq, lin)
+
+
+# ---------------------------------------------------------------- gemv, batch 1
+def test_gemv_config0(ptq):
+    lin, x = workloads.config0()
+    y = ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), 1024, 1024)
+    worst = check(y, lin, x)
+    print(f"config0 max err/B = {worst:.3e}")
+
+
+@pytest.mark.parametrize("N,K", [(16, 128), (16, 256), (48, 384), (1000, 1024), (257, 4096), (7, 640),
+                                  (640, 2048), (96, 14336), (2048, 8192), (64, 28672)])
+def test_gemv_shapes(ptq, N, K):
+    lin = workloads.make_linear(N, K, 53, N, K)
+    x = workloads.make_x(1, K, 53, N, K)
+    y = ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), N, K)
+    check(y, lin, x)
+
+
+@pytest.mark.parametrize("waves,rows", [(1, 1), (3, 2), (16, 4), (5, 1), (16, 2)])
+def test_gemv_launch_shapes(ptq, waves, rows):
+    # every launch shape the tuning hook can select computes the same layer
+    lin = workloads.make_linear(200, 2304, 54)
+    x = workloads.make_x(1, 2304, 54)
+    packed = pack(ptq, lin)
+    try:
+        ptq.ptqtp_tune("gemv_waves", waves)
+        ptq.ptqtp_tune("gemv_rows", rows)
+        y = ptq.ptqtp_gemv(packed, dev(x).reshape(-1), 200, 2304)
+        check(y, lin, x)
+        xm = workloads.make_x(9, 2304, 54, 9)
+        check(ptq.ptqtp_gemm_small(packed, dev(xm), 200, 2304), lin, xm)
+    finally:
+        ptq.ptqtp_tune("gemv_waves", 0)
+        ptq.ptqtp_tune("gemv_rows", 0)
+
+
+def test_gemv_unit_vectors_exact(ptq):
+    # x = e_j returns column j of W^ = a1 T1 + a2 T2; with a2/a1 in [0.1, 0.5] the sum is exact in fp32
+    N, K = 80, 768
+    lin = workloads.make_linear(N, K, 55)
+    packed = pack(ptq, lin)
+    W = oracle.reconstruct_dense(lin["T1"], lin["T2"], lin["a1"], lin["a2"])
+    cols = sorted(set([0, 1, 2, 7, 8, 31, 32, 127, 128, 255, 256, 257, 511, 767] + list(range(300, 364))))
+    for j in cols:
+        e = np.zeros((1, K), dtype=np.float16)
+        e[0, j] = 1.0
+        y = ptq.ptqtp_gemv(packed, dev(e).reshape(-1), N, K).cpu().numpy().astype(np.float64)
+        assert np.array_equal(y[0], W[:, j].astype(np.float32).astype(np.float64)), f"column {j}"
+        assert np.array_equal(W[:, j].astype(np.float32).astype(np.float64), W[:, j])
+
+
+@pytest.mark.parametrize("M", [1, 5, 16, 33])
+def test_integer_exact_bitwise(ptq, M):
+    # every partial sum is exactly representable, so any summation order gives the oracle's bits
+    N, K = 208, 3072
+    lin, x = workloads.integer_exact_case(N, K, M, 56, M)
+    y_ref, _ = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+    y = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K).cpu().numpy().astype(np.float64)
+    assert np.array_equal(y, y_ref)
+
+
+def test_gemv_zero_bound_gives_exact_zero(ptq):
+    N, K = 64, 512
+    lin = workloads.make_linear(N, K, 57)
+    x = workloads.make_x(1, K, 57)
+    lin["T1"][3, :] = 0
+    lin["T2"][3, :] = 0                     # empty row
+    lin["a1"][9, :] = 0
+    lin["a2"][9, :] = 0                     # zero scales
+    lin["T1"][11, 128:] = 0
+    lin["T2"][11, 128:] = 0
+    xz = x.copy()
+    xz[0, :128] = 0                          # row 11 only meets zeros
+    packed = pack(ptq, lin)
+    y = ptq.ptqtp_gemv(packed, dev(xz).reshape(-1), N, K)
+    check(y, lin, xz)
+    yn = y.cpu().numpy()
+    assert yn[0, 3] == 0 and yn[0, 9] == 0 and yn[0, 11] == 0
+    y0 = ptq.ptqtp_gemv(packed, dev(np.zeros((1, K), np.float16)).reshape(-1), N, K)
+    assert torch.count_nonzero(y0).item() == 0
+
+
+def test_gemv_general_scales_and_subnormal_x(ptq):
+    N, K = 96, 1024
+    lin = workloads.make_linear(N, K, 58)
+    r = np.random.default_rng(58)
+    lin["a1"] = (r.standard_normal((N, K // 128)) * 3).astype(np.float16)        # signed, large
+    lin["a2"] = (r.standard_normal((N, K // 128)) * 1e-6).astype(np.float16)     # subnormal fp16
+    x = workloads.make_x(1, K, 58)
+    x[0, ::3] = (r.standard_normal(len(x[0, ::3])) * 2e-6).astype(np.float16)    # subnormal activations
+    x[0, 5] = np.float16(60000.0)
+    x[0, 700] = np.float16(-30000.0)
+    y = ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), N, K)
+    check(y, lin, x)
+    xs = (r.standard_normal((1, K)) * 3e-6).astype(np.float16)                   # all subnormal
+    check(ptq.ptqtp_gemv(pack(ptq, lin), dev(xs).reshape(-1), N, K), lin, xs)
+
+
+def test_gemv_fp16_output(ptq):
+    lin, x = workloads.config0()
+    y = ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), 1024, 1024, y_dtype=ptq.PTQTP_F16)
+    assert y.dtype == torch.float16
+    check(y, lin, x, tight=TIGHT_F16)
+
+
+def test_gemv_deterministic_and_in_bounds(ptq):
+    N, K = 1000, 4096
+    lin = workloads.make_linear(N, K, 59)
+    x = dev(workloads.make_x(1, K, 59)).reshape(-1)
+    packed = pack(ptq, lin)
+    guard = 64
+    buf = torch.full((N + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda:0")
+    out = buf[guard:guard + N].view(1, N)
+    first = None
+    for _ in range(20):
+        ptq.ptqtp_gemv(packed, x, N, K, out=out)
+        cur = out.clone()
+        if first is None:
+            first = cur
+        assert torch.equal(cur.view(torch.int32), first.view(torch.int32))
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[guard + N:]).all()
+    assert not torch.isnan(out).any()
+
+
+# ---------------------------------------------------------------- small batch
+@pytest.mark.parametrize("M", [2, 4, 15, 16, 17, 32, 48, 64])
+def test_gemm_small_batches(ptq, M):
+    N, K = 528, 2048
+    lin = workloads.make_linear(N, K, 60)
+    x = workloads.make_x(M, K, 60, M)
+    y = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K)
+    check(y, lin, x)
+
+
+@pytest.mark.parametrize("N,K,M", [(1000, 1024, 4), (257, 4096, 16), (48, 384, 64), (16, 128, 3), (96, 14336, 24)])
+def test_gemm_small_shapes(ptq, N, K, M):
+    lin = workloads.make_linear(N, K, 61, N, K)
+    x = workloads.make_x(M, K, 61, N, M)
+    check(ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K), lin, x)
+
+
+def test_gemm_small_rows_match_gemv(ptq):
+    # each token of a batch gets the bits batch-1 would give it? not required (different
+    # reduction trees are both correct) -- but both must sit inside the tight gate
+    N, K = 320, 4096
+    lin = workloads.make_linear(N, K, 62)
+    x = workloads.make_x(16, K, 62)
+    packed = pack(ptq, lin)
+    yb = ptq.ptqtp_gemm_small(packed, dev(x), N, K)
+    check(yb, lin, x)
+    for m in (0, 7, 15):
+        y1 = ptq.ptqtp_gemv(packed, dev(x[m]), N, K)
+        check(y1, lin, x[m:m + 1])
+
+
+def test_gemm_small_fp16_output_and_guard(ptq):
+    N, K, M = 200, 1024, 7
+    lin = workloads.make_linear(N, K, 63)
+    x = workloads.make_x(M, K, 63)
+    buf = torch.full((M * N + 128,), 7.0, dtype=torch.float16, device="cuda:0")
+    out = buf[64:64 + M * N].view(M, N)
+    ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K, y_dtype=ptq.PTQTP_F16, out=out)
+    check(out, lin, x, tight=TIGHT_F16)
+    assert (buf[:64] == 7).all() and (buf[64 + M * N:] == 7).all()
+
+
+# ---------------------------------------------------------------- full-size layers, sampled rows
+def _sampled_rows_check(ptq, lin, x, y, rows):
+    sub_ref, B = oracle.forward(lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows], x, threads=8)
+    got = y.cpu().numpy().astype(np.float64)[:, rows]
+    err = np.abs(got - sub_ref)
+    assert np.all(err <= TOL * B) and np.all(err <= TIGHT * B), f"{(err / B).max():.3e}"
+
+
+@pytest.mark.parametrize("name", ["q", "k", "gate", "down"])
+def test_gemv_8b_shapes_sampled(ptq, name):
+    lin = workloads.linear_8b(name)
+    N, K = lin["N"], lin["K"]
+    x = workloads.x_for(name, 1, K)
+    packed = pack(ptq, lin)
+    y = ptq.ptqtp_gemv(packed, dev(x).reshape(-1), N, K)
+    rows = np.unique(np.concatenate([np.arange(0, 32), np.arange(N - 32, N),
+                                     np.random.default_rng(1).integers(0, N, 448)]))
+    _sampled_rows_check(ptq, lin, x, y, rows)
+    # properties that hold at any size: determinism and linearity in x (2x is exact in fp16/fp32)
+    y2 = ptq.ptqtp_gemv(packed, dev(x * np.float16(2)).reshape(-1), N, K)
+    assert torch.equal(y2, 2 * y)
+    assert torch.equal(ptq.ptqtp_gemv(packed, dev(x).reshape(-1), N, K), y)
+
+
+@pytest.mark.parametrize("M", [4, 16, 64])
+def test_gemm_small_8b_q_sampled(ptq, M):
+    lin = workloads.linear_8b("q")
+    N, K = lin["N"], lin["K"]
+    x = workloads.x_for("q", M, K, config=2)
+    y = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K)
+    rows = np.unique(np.concatenate([np.arange(0, 16), np.arange(N - 16, N),
+                                     np.random.default_rng(2).integers(0, N, 224)]))
+    _sampled_rows_check(ptq, lin, x, y, rows)
+
+
+def test_gemv_70b_shapes_sampled(ptq):
+    for name in ("k", "down"):
+        lin = workloads.linear_70b(name)
+        N, K = lin["N"], lin["K"]
+        x = workloads.x_for(name, 1, K, config=4)
+        y = ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), N, K)
+        rows = np.unique(np.random.default_rng(3).integers(0, N, 256))
+        _sampled_rows_check(ptq, lin, x, y, rows)
+        if name == "down":
+            x32 = workloads.x_for(name, 32, K, config=4)
+            y32 = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x32), N, K)
+            _sampled_rows_check(ptq, lin, x32, y32, rows[:64])
+
+
+def test_smoke_entry(ptq):
+    import __graft_entry__
+    __graft_entry__.smoke()
