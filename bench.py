@@ -32,47 +32,19 @@ def algorithmic_bytes(N: int, K: int, M: int = 1, group: int = 128) -> int:
     return N * K // 2 + 4 * N * (K // group) + 2 * M * K + 4 * M * N
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--layers", type=int, default=32)
-    ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
-                    help="graph: one hipGraph replay per step; eager: 7*layers library calls per step")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--per-shape", action="store_true", help="also time every shape on its own (hot and cold)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path needs no second device); use --gpus 1",
-              file=sys.stderr)
-        return 2
-
-    import numpy as np
-    import torch
-
-    import paper_2509_16989_amd as ptq
-    import workloads
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    names = workloads.LINEAR_ORDER
-    shapes = workloads.SHAPES_8B
-
-    # ---- build the stack: generate on the host (seeded recipe), pack on the device ----------
+def build_stack(ptq, torch, workloads, layers: int, dev, log=True):
+    """Generate (seeded recipe, host) and pack (device) `layers` x 7 linears.  Returns the
+    per-linear blobs, activations, outputs, (layer, name) jobs, shapes, and layer 0's host copy."""
     t0 = time.time()
+    names = workloads.LINEAR_ORDER
     pool = ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1))
-    jobs = [(layer, name) for layer in range(args.layers) for name in names]
+    jobs = [(layer, name) for layer in range(layers) for name in names]
 
     def gen(job):
-        layer, name = job
-        return workloads.linear_8b(name, layer)
+        return workloads.linear_8b(job[1], job[0])
 
     blobs, xs, ys = [], [], []
-    layer0 = None
+    layer0 = {}
     window = 14
     pending = [pool.submit(gen, j) for j in jobs[:window]]
     nxt = window
@@ -87,56 +59,102 @@ def main() -> int:
         xs.append(torch.from_numpy(workloads.x_for(job[1], 1, K, 1, job[0])).to(dev).reshape(-1))
         ys.append(torch.empty((1, N), dtype=torch.float32, device=dev))
         if job[0] == 0:
-            layer0 = layer0 or {}
             layer0[job[1]] = lin
-        if idx % 28 == 27:
+        if log and idx % 56 == 55:
             print(f"[bench] packed {idx + 1}/{len(jobs)} linears ({time.time() - t0:.0f} s)", file=sys.stderr, flush=True)
     pool.shutdown()
     torch.cuda.synchronize()
-    dims = [shapes[name] for _, name in jobs]
-    bytes_step = sum(algorithmic_bytes(n, k) for n, k in dims)
-    launches_step = len(jobs)
+    dims = [workloads.SHAPES_8B[name] for _, name in jobs]
+    return blobs, xs, ys, jobs, dims, layer0
 
-    def run_step():
+
+def make_step(ptq, torch, mode, blobs, xs, ys, dims, stream):
+    """A callable that enqueues one decode step on `stream` (must be the current stream)."""
+    def run_calls():
         for blob, x, y, (n, k) in zip(blobs, xs, ys, dims):
             ptq.ptqtp_gemv(blob, x, n, k, out=y)
 
+    if mode == "eager":
+        return run_calls, len(blobs)
+    if mode == "graph":
+        run_calls()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run_calls()
+        return graph.replay, len(blobs)
+    plan = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xs, ys, dims)])
+    stream.synchronize()
+    return (lambda: ptq.ptqtp_gemv_batch(plan)), 1
+
+
+def time_steps(torch, step, steps, warmup, stream):
+    for _ in range(warmup):
+        step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(steps):
+        step()
+    ev1.record(stream)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    return max(ev0.elapsed_time(ev1), wall * 1e3) / steps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--mode", choices=["batch", "graph", "eager"], default="batch",
+                    help="batch: one ptqtp_gemv_batch launch per step; graph: 7*layers ptqtp_gemv launches "
+                         "replayed as one hipGraph; eager: the same launches issued call by call")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-shape", action="store_true", help="also time every shape on its own (hot and cold)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path needs no second device); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2509_16989_amd as ptq
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    names = workloads.LINEAR_ORDER
+
+    blobs, xs, ys, jobs, dims, layer0 = build_stack(ptq, torch, workloads, args.layers, dev)
+    bytes_step = sum(algorithmic_bytes(n, k) for n, k in dims)
+
     stream = torch.cuda.Stream()          # default priority
-    graph = None
+    extra = {}
     with torch.cuda.stream(stream):
-        run_step()
-        stream.synchronize()
-        if args.mode == "graph":
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                run_step()
-        step = graph.replay if graph is not None else run_step
+        step, launches_step = make_step(ptq, torch, args.mode, blobs, xs, ys, dims, stream)
+        ms_per_step = time_steps(torch, step, args.steps, args.warmup, stream)
+        others = {}
+        for mode in ("batch", "graph"):
+            if mode != args.mode:
+                st, _ = make_step(ptq, torch, mode, blobs, xs, ys, dims, stream)
+                others[mode] = round(time_steps(torch, st, max(3, args.steps // 5), 2, stream) * 1e3, 2)
+        extra["us_per_decode_step_other_modes"] = others
+        if args.per_shape:
+            extra["per_shape"] = per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream)
 
-        for _ in range(args.warmup):
-            step()
-        stream.synchronize()
-        torch.cuda.synchronize()
-        ev0 = torch.cuda.Event(enable_timing=True)
-        ev1 = torch.cuda.Event(enable_timing=True)
-        wall0 = time.perf_counter()
-        ev0.record(stream)
-        for _ in range(args.steps):
-            step()
-        ev1.record(stream)
-        stream.synchronize()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - wall0
-        gpu_ms = ev0.elapsed_time(ev1)
-
-    ms_per_step = max(gpu_ms, wall * 1e3) / args.steps
     gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
     launch_us = ms_per_step * 1e3 / launches_step
     bytes_launch = bytes_step / launches_step
-
-    extra = {}
-    if args.per_shape:
-        extra["per_shape"] = per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream)
-
     out = {
         "metric": "ternary GEMV effective HBM GB/s, 8B shapes b=1 (one decode step through the stack)",
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -151,7 +169,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": round(bytes_launch / (launch_us * 1e-6) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(bytes_launch / (launch_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "gemv_kernel<1,1,true>", "avg_launch_us": round(launch_us, 3),
+                     "kernel": "gemv_items_kernel", "avg_launch_us": round(launch_us, 3),
                      "bytes_per_launch": round(bytes_launch)},
     }
     out.update(extra)

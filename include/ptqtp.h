@@ -128,9 +128,43 @@ ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, in
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Many independent batch-1 layers in ONE launch (fused q/k/v, gate/up, or a whole
+ * stack of layers whose inputs are all known): the same sum as ptqtp_gemv for each
+ * entry.  One launch covers every 16-row tile of every entry, so the HBM stream does
+ * not drain between layers and small layers share the chip with their neighbours.
+ *
+ * ptqtp_gemv_batch_plan writes a small device-side table (one-time, stream-ordered):
+ *   linears     HOST array of `count` entries; every pointer inside is a device
+ *               pointer with the meaning and alignment it has in ptqtp_gemv; the
+ *               entries' y buffers must not overlap each other or any x
+ *   plan        device, receives ptqtp_batch_plan_bytes(linears,count,group) bytes,
+ *               256-byte aligned
+ * ptqtp_gemv_batch runs the plan: `items` must be ptqtp_batch_items(...) of the same
+ * list (= sum over entries of ceil(N/16), the number of workgroups).  The plan may be
+ * re-run any number of times and stays valid while the buffers it names are alive.
+ * ptqtp_batch_plan_bytes and ptqtp_batch_items return 0 for invalid arguments.
+ */
+#define PTQTP_BATCH_MAX_LINEARS 4096
+typedef struct ptqtp_linear {
+    const void *packed;     /* device, blob from ptqtp_pack for this N, K */
+    const uint16_t *x;      /* device, fp16 bits [K] */
+    void *y;                /* device, [N] of the plan's y_dtype */
+    int64_t N, K;
+} ptqtp_linear;
+
+size_t ptqtp_batch_plan_bytes(const ptqtp_linear *linears, int32_t count, int32_t group);
+int64_t ptqtp_batch_items(const ptqtp_linear *linears, int32_t count, int32_t group);
+ptqtp_status ptqtp_gemv_batch_plan(const ptqtp_linear *linears, int32_t count, int32_t y_dtype, int32_t group,
+                                   void *plan, size_t plan_bytes, void *stream);
+ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream);
+
+/*
  * Tuning hook for benchmarks and sweeps (not needed for correct use): override
  * the launch shape the compute calls pick.  key = "gemv_waves" (waves per
- * workgroup, 1..16), "gemv_rows" (16-row tiles per workgroup, 1, 2 or 4);
+ * workgroup, 1..16), "gemv_rows" (16-row tiles per workgroup, 1, 2 or 4),
+ * "gemv_stream" (batch 1: 1 = item kernel, 0 = tiled kernel, -1 = default),
+ * "stream_waves" (waves per item, 1..16), "stream_depth" (records in flight per
+ * wave: 1, 2 or 4);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
  * unknown key or out-of-range value.  Not thread-safe.
  */

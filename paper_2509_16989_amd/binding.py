@@ -53,6 +53,14 @@ def _load():
         lib.ptqtp_gemv.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
         lib.ptqtp_gemm_small.restype = i32
         lib.ptqtp_gemm_small.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
+        lib.ptqtp_batch_plan_bytes.restype = sz
+        lib.ptqtp_batch_plan_bytes.argtypes = [p, i32, i32]
+        lib.ptqtp_batch_items.restype = i64
+        lib.ptqtp_batch_items.argtypes = [p, i32, i32]
+        lib.ptqtp_gemv_batch_plan.restype = i32
+        lib.ptqtp_gemv_batch_plan.argtypes = [p, i32, i32, i32, p, sz, p]
+        lib.ptqtp_gemv_batch.restype = i32
+        lib.ptqtp_gemv_batch.argtypes = [p, i64, p]
         lib.ptqtp_tune.restype = i32
         lib.ptqtp_tune.argtypes = [ctypes.c_char_p, i32]
         _lib = lib
@@ -150,3 +158,42 @@ def ptqtp_gemm_small(packed, x, N: int, K: int, group: int = 128, y_dtype: int =
     if x.dim() != 2 or x.shape[1] != K:
         raise PtqtpError(2, "ptqtp_gemm_small")
     return _forward(_load().ptqtp_gemm_small, "ptqtp_gemm_small", packed, x, N, K, x.shape[0], group, y_dtype, out)
+
+
+class _Linear(ctypes.Structure):
+    _fields_ = [("packed", ctypes.c_void_p), ("x", ctypes.c_void_p), ("y", ctypes.c_void_p),
+                ("N", ctypes.c_int64), ("K", ctypes.c_int64)]
+
+
+class BatchPlan:
+    """Device-side table for ptqtp_gemv_batch; keeps the tensors it names alive."""
+
+    def __init__(self, plan: torch.Tensor, items: int, keep):
+        self.plan, self.items, self._keep = plan, items, keep
+
+
+def ptqtp_gemv_batch_plan(linears, group: int = 128, y_dtype: int = PTQTP_F32) -> BatchPlan:
+    """linears: sequence of (packed, x, y, N, K) with torch tensors; y [1,N] or [N] of y_dtype."""
+    ydt = torch.float32 if y_dtype == PTQTP_F32 else torch.float16
+    n = len(linears)
+    arr = (_Linear * max(n, 1))()
+    for i, (packed, x, y, N, K) in enumerate(linears):
+        if x.numel() != K or y.numel() != N:
+            raise PtqtpError(2, "ptqtp_gemv_batch_plan")
+        arr[i] = _Linear(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"), _dev(y, ydt, "y"), N, K)
+    lib = _load()
+    nbytes = int(lib.ptqtp_batch_plan_bytes(arr, n, group))
+    items = int(lib.ptqtp_batch_items(arr, n, group))
+    if nbytes == 0 or items == 0:
+        raise PtqtpError(2, "ptqtp_batch_plan_bytes")
+    plan = torch.empty(nbytes, dtype=torch.uint8, device=linears[0][0].device)
+    st = lib.ptqtp_gemv_batch_plan(arr, n, y_dtype, group, plan.data_ptr(), nbytes, _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_gemv_batch_plan")
+    return BatchPlan(plan, items, [t for lin in linears for t in lin[:3]])
+
+
+def ptqtp_gemv_batch(plan: BatchPlan) -> None:
+    st = _load().ptqtp_gemv_batch(plan.plan.data_ptr(), plan.items, _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_gemv_batch")

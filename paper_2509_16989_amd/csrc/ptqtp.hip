@@ -324,6 +324,177 @@ gemv_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x,
     }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// batch-1 kernel over a list of (linear, 16-row tile) items
+// ------------------------------------------------------------------------------------------
+// One workgroup = one item = one 16-row tile of one linear over its whole K.  Its W waves split
+// the item's 256-column steps (wave w: ks = w, w+W, ...).  A wave issues the loads of up to S
+// steps at once (straight-line code, so every wait is an exact vmcnt), consumes them, and
+// repeats; latency is hidden by the other workgroups resident on the CU.  Partial sums meet in
+// LDS in fixed order.  A plan (table of linears + item -> linear map) lets one launch cover many
+// linears, so the HBM stream does not drain between the layers of a stack.
+struct LinearDesc {
+    const uint8_t *records;   // blob + header
+    const uint16_t *x;        // fp16 [K]
+    void *y;                  // [N] f32 or f16
+    int32_t N, K, RT, KS;
+    int32_t first_item;       // index of this linear's row tile 0 in the item list
+    int32_t pad;
+};
+
+struct PlanHeader {           // 64 bytes, followed by LinearDesc[count], then int32 item_lin[total_items]
+    uint64_t magic;
+    int32_t count, total_items, y_f16, group;
+    int32_t reserved[10];
+};
+constexpr uint64_t kPlanMagic = 0x314e4c5050545150ull;  // "PQTPPLN1"
+constexpr int kPlanChunk = 32;
+
+struct DescChunk { LinearDesc d[kPlanChunk]; };
+
+__global__ void plan_write_kernel(PlanHeader *plan, DescChunk chunk, int base, int n, int count, int total_items,
+                                  int y_f16)
+{
+    const int t = threadIdx.x;
+    if (base == 0 && t == 0) {
+        PlanHeader h = {};
+        h.magic = kPlanMagic; h.count = count; h.total_items = total_items; h.y_f16 = y_f16; h.group = 128;
+        *plan = h;
+    }
+    if (t < n) reinterpret_cast<LinearDesc *>(plan + 1)[base + t] = chunk.d[t];
+}
+
+// item -> linear index, by bisection over first_item (one-time, after plan_write_kernel)
+__global__ void __launch_bounds__(256) plan_map_kernel(PlanHeader *plan)
+{
+    const int count = plan->count, total = plan->total_items;
+    LinearDesc *table = reinterpret_cast<LinearDesc *>(plan + 1);
+    int32_t *map = reinterpret_cast<int32_t *>(table + count);
+    for (int item = blockIdx.x * 256 + threadIdx.x; item < total; item += gridDim.x * 256) {
+        int lo = 0, hi = count - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (table[mid].first_item <= item) lo = mid; else hi = mid - 1;
+        }
+        map[item] = lo;
+    }
+}
+
+// Load through the global address space (descriptor pointers come out of memory and would
+// otherwise be treated as generic: flat loads tie up the LDS counter as well).
+template <class T>
+__device__ __forceinline__ T load_global(const void *p) {
+    return *(const __attribute__((address_space(1))) T *)(p);
+}
+
+struct StepRegs {             // one record + its activation slice
+    uintx4 p1, p2;
+    uintx2 sc, xr;
+};
+
+template <bool PLAN, int S>
+__global__ void __launch_bounds__(1024)
+gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int single_f16)
+{
+    __shared__ float red[16][16];
+    __shared__ uintx2 xs[16][64];
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int W = blockDim.x >> 6;
+    const int nl = lane & 15, q = lane >> 4;
+    const int item = blockIdx.x;
+
+    const LinearDesc *dp = &single;
+    int y_f16 = single_f16;
+    if (PLAN) {
+        const LinearDesc *table = reinterpret_cast<const LinearDesc *>(plan + 1);
+        const int32_t *map = reinterpret_cast<const int32_t *>(table + plan->count);
+        if (item >= plan->total_items) return;      // whole workgroup leaves: no barrier is skipped
+        dp = table + map[item];
+        y_f16 = plan->y_f16;
+    }
+    const int K = dp->K, KS = dp->KS, N = dp->N;
+    const int rt = item - dp->first_item;
+    const uint8_t *rec0 = dp->records + static_cast<size_t>(rt) * KS * kRecordBytes;
+    const uint16_t *x = dp->x;
+
+    uintx4 xa[1][8];
+#pragma unroll
+    for (int f = 0; f < 8; ++f) xa[0][f] = uintx4{0, 0, 0, 0};   // lanes of tokens 1..15 stay zero
+    const char *xs_rd = reinterpret_cast<const char *>(&xs[w][0]) + q * 64;
+    float yacc = 0.f;
+
+    for (int ks0 = w; ks0 < KS; ks0 += S * W) {
+        StepRegs r[S];
+        // issue: S steps in flight.  Steps past the end re-read the wave's first step (address
+        // stays valid, result unused) so that the number of outstanding loads is static.
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            const int ks = ks0 + i * W;
+            const int kse = ks < KS ? ks : ks0;
+            const uint8_t *rec = rec0 + static_cast<size_t>(kse) * kRecordBytes;
+            r[i].p1 = load_global<uintx4>(rec + lane * 16);
+            r[i].p2 = load_global<uintx4>(rec + kPlaneBytes + lane * 16);
+            r[i].sc = load_global<uintx2>(rec + 2 * kPlaneBytes + nl * 8);
+            int k = kse * kStepK + lane * 4;
+            k = k < K ? k : 0;                                   // odd number of groups: tail lanes
+            r[i].xr = load_global<uintx2>(x + k);
+        }
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            const int ks = ks0 + i * W;
+            if (ks < KS) {
+                uintx2 xr = r[i].xr;
+                if (ks * kStepK + lane * 4 >= K) xr = uintx2{0, 0};
+                xs[w][lane] = xr;                                // wave-private bounce: no barrier
+                if (nl == 0) {
+#pragma unroll
+                    for (int f = 0; f < 8; ++f)
+                        xa[0][f] = *reinterpret_cast<const uintx4 *>(xs_rd + (f >> 2) * 256 + (f & 3) * 16);
+                }
+                const float a1g0 = half_bits_to_float(r[i].sc.x & 0xffffu), a1g1 = half_bits_to_float(r[i].sc.x >> 16);
+                const float a2g0 = half_bits_to_float(r[i].sc.y & 0xffffu), a2g1 = half_bits_to_float(r[i].sc.y >> 16);
+                floatx4 acc[1];
+                group_sum<1, 0>(xa, r[i].p1, acc); yacc = fmaf(a1g0, acc[0][0], yacc);
+                group_sum<1, 1>(xa, r[i].p1, acc); yacc = fmaf(a1g1, acc[0][0], yacc);
+                group_sum<1, 0>(xa, r[i].p2, acc); yacc = fmaf(a2g0, acc[0][0], yacc);
+                group_sum<1, 1>(xa, r[i].p2, acc); yacc = fmaf(a2g1, acc[0][0], yacc);
+            }
+        }
+    }
+
+    if (q == 0) red[w][nl] = yacc;
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        float s = 0.f;
+        for (int ww = 0; ww < W; ++ww) s += red[ww][threadIdx.x];
+        s *= 0.5f;   // trits were decoded as +-2.0
+        const int n = rt * kTileRows + threadIdx.x;
+        if (n < N) {
+            if (y_f16) reinterpret_cast<_Float16 *>(dp->y)[n] = static_cast<_Float16>(s);
+            else reinterpret_cast<float *>(dp->y)[n] = s;
+        }
+    }
+}
+
+int g_tune_stream = -1;      // -1/1: item kernel for batch 1, 0: tiled kernel
+int g_tune_stream_waves = 0, g_tune_stream_depth = 0;
+
+template <bool PLAN>
+hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_f16, int64_t total_items,
+                        hipStream_t stream)
+{
+    const int W = g_tune_stream_waves > 0 ? g_tune_stream_waves : 4;
+    const int S = g_tune_stream_depth > 0 ? g_tune_stream_depth : 4;
+    const dim3 grid(static_cast<unsigned>(total_items)), block(W * 64);
+    if (S >= 4) hipLaunchKernelGGL((gemv_items_kernel<PLAN, 4>), grid, block, 0, stream, plan, single, y_f16);
+    else if (S >= 2) hipLaunchKernelGGL((gemv_items_kernel<PLAN, 2>), grid, block, 0, stream, plan, single, y_f16);
+    else hipLaunchKernelGGL((gemv_items_kernel<PLAN, 1>), grid, block, 0, stream, plan, single, y_f16);
+    return hipGetLastError();
+}
+
 int g_tune_waves = 0, g_tune_rows = 0;
 
 template <int MT, int R, bool SINGLE>
@@ -360,7 +531,14 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
     const uint8_t *records = static_cast<const uint8_t *>(packed) + kHeaderBytes;
     const int Mi = static_cast<int>(M), f16 = (y_dtype == PTQTP_F16);
     hipError_t e;
-    if (M == 1) {
+    if (M == 1 && g_tune_stream != 0) {
+        LinearDesc d;
+        d.records = records; d.x = x; d.y = y;
+        d.N = static_cast<int32_t>(s.N); d.K = static_cast<int32_t>(s.K);
+        d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
+        d.first_item = 0; d.pad = 0;
+        e = launch_items<false>(nullptr, d, f16, s.RT, stream);
+    } else if (M == 1) {
         const int W = pick_waves(s.KS, 16);
         int R = g_tune_rows > 0 ? g_tune_rows : (s.RT >= 4096 ? 2 : 1);
         if (R >= 4) e = launch_gemv<1, 4, true>(records, x, y, Mi, s, W, f16, stream);
@@ -465,8 +643,98 @@ ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, in
     return run_forward(packed, x, y, y_dtype, M, N, K, group, stream);
 }
 
+static ptqtp_status plan_items(const ptqtp_linear *linears, int32_t count, int32_t group, int64_t *total) {
+    if (!linears) return PTQTP_ERR_NULL;
+    if (count <= 0 || count > PTQTP_BATCH_MAX_LINEARS) return PTQTP_ERR_SHAPE;
+    *total = 0;
+    for (int i = 0; i < count; ++i) {
+        Shape s;
+        ptqtp_status st;
+        if (!make_shape(1, linears[i].N, linears[i].K, group, &s, &st)) return st;
+        *total += s.RT;
+    }
+    return *total > (1ll << 30) ? PTQTP_ERR_SHAPE : PTQTP_OK;
+}
+
+size_t ptqtp_batch_plan_bytes(const ptqtp_linear *linears, int32_t count, int32_t group) {
+    int64_t total;
+    if (plan_items(linears, count, group, &total) != PTQTP_OK) return 0;
+    return sizeof(PlanHeader) + static_cast<size_t>(count) * sizeof(LinearDesc) + static_cast<size_t>(total) * 4;
+}
+
+ptqtp_status ptqtp_gemv_batch_plan(const ptqtp_linear *linears, int32_t count, int32_t y_dtype, int32_t group,
+                                   void *plan, size_t plan_bytes, void *stream_)
+{
+    int64_t total = 0;
+    if (!plan) return PTQTP_ERR_NULL;
+    ptqtp_status st = plan_items(linears, count, group, &total);
+    if (st != PTQTP_OK) return st;
+    if (y_dtype != PTQTP_F32 && y_dtype != PTQTP_F16) return PTQTP_ERR_DTYPE;
+    if (plan_bytes < ptqtp_batch_plan_bytes(linears, count, group)) return PTQTP_ERR_SIZE;
+    if (!aligned(plan, 256)) return PTQTP_ERR_ALIGN;
+    for (int i = 0; i < count; ++i) {
+        if (!linears[i].packed || !linears[i].x || !linears[i].y) return PTQTP_ERR_NULL;
+        if (!aligned(linears[i].packed, 256) || !aligned(linears[i].x, 16) ||
+            !aligned(linears[i].y, y_dtype == PTQTP_F16 ? 2 : 4))
+            return PTQTP_ERR_ALIGN;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int64_t first = 0;
+    for (int base = 0; base < count; base += kPlanChunk) {
+        DescChunk chunk = {};
+        const int n = count - base < kPlanChunk ? count - base : kPlanChunk;
+        for (int i = 0; i < n; ++i) {
+            Shape s;
+            make_shape(1, linears[base + i].N, linears[base + i].K, group, &s, &st);
+            LinearDesc &d = chunk.d[i];
+            d.records = static_cast<const uint8_t *>(linears[base + i].packed) + kHeaderBytes;
+            d.x = linears[base + i].x; d.y = linears[base + i].y;
+            d.N = static_cast<int32_t>(s.N); d.K = static_cast<int32_t>(s.K);
+            d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
+            d.first_item = static_cast<int32_t>(first); d.pad = 0;
+            first += s.RT;
+        }
+        hipLaunchKernelGGL(plan_write_kernel, dim3(1), dim3(64), 0, stream, static_cast<PlanHeader *>(plan), chunk,
+                           base, n, count, static_cast<int>(total), y_dtype == PTQTP_F16 ? 1 : 0);
+    }
+    const unsigned blocks = static_cast<unsigned>(total + 255) / 256;
+    hipLaunchKernelGGL(plan_map_kernel, dim3(blocks > 1024 ? 1024 : blocks), dim3(256), 0, stream,
+                       static_cast<PlanHeader *>(plan));
+    return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
+int64_t ptqtp_batch_items(const ptqtp_linear *linears, int32_t count, int32_t group) {
+    int64_t total;
+    return plan_items(linears, count, group, &total) == PTQTP_OK ? total : 0;
+}
+
+ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream_) {
+    if (!plan) return PTQTP_ERR_NULL;
+    if (!aligned(plan, 256)) return PTQTP_ERR_ALIGN;
+    if (items <= 0 || items > (1ll << 30)) return PTQTP_ERR_SHAPE;
+    LinearDesc none = {};
+    const hipError_t e = launch_items<true>(static_cast<const PlanHeader *>(plan), none, 0, items,
+                                            static_cast<hipStream_t>(stream_));
+    return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
 ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!key) return PTQTP_ERR_NULL;
+    if (!strcmp(key, "gemv_stream")) {
+        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
+        g_tune_stream = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "stream_waves")) {
+        if (value < 0 || value > 16) return PTQTP_ERR_SHAPE;
+        g_tune_stream_waves = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "stream_depth")) {
+        if (value != 0 && value != 1 && value != 2 && value != 4) return PTQTP_ERR_SHAPE;
+        g_tune_stream_depth = value;
+        return PTQTP_OK;
+    }
     if (!strcmp(key, "gemv_waves")) {
         if (value < 0 || value > 16) return PTQTP_ERR_SHAPE;
         g_tune_waves = value;

@@ -50,6 +50,33 @@ def test_packed_bytes_closed_form(lib):
     assert lib.ptqtp_workspace_bytes(1, 4096, 4096, 128) == 0
 
 
+def test_batch_plan_validation(lib):
+    from paper_2509_16989_amd.binding import _Linear
+    arr = (_Linear * 3)()
+    arr[0] = _Linear(0x10000, 0x20000, 0x30000, 4096, 4096)
+    arr[1] = _Linear(0x10000, 0x20000, 0x30000, 1000, 1024)
+    arr[2] = _Linear(0x10000, 0x20000, 0x30000, 16, 128)
+    items = 256 + 63 + 1
+    assert lib.ptqtp_batch_items(arr, 3, 128) == items
+    assert lib.ptqtp_batch_plan_bytes(arr, 3, 128) == 64 + 3 * 48 + 4 * items
+    assert lib.ptqtp_batch_items(arr, 0, 128) == 0
+    assert lib.ptqtp_batch_items(arr, 3, 64) == 0
+    assert lib.ptqtp_batch_items(None, 3, 128) == 0
+    fake = ctypes.c_void_p(0x40000)
+    assert lib.ptqtp_gemv_batch_plan(arr, 3, 0, 128, fake, 10, None) == 4          # plan buffer too small
+    assert lib.ptqtp_gemv_batch_plan(arr, 3, 9, 128, fake, 1 << 20, None) == 5
+    assert lib.ptqtp_gemv_batch_plan(arr, 3, 0, 128, None, 1 << 20, None) == 1
+    arr[1].K = 1000
+    assert lib.ptqtp_gemv_batch_plan(arr, 3, 0, 128, fake, 1 << 20, None) == 2
+    arr[1].K = 1024
+    arr[2].x = 0
+    assert lib.ptqtp_gemv_batch_plan(arr, 3, 0, 128, fake, 1 << 20, None) == 1
+    arr[2].x = 0x20002
+    assert lib.ptqtp_gemv_batch_plan(arr, 3, 0, 128, fake, 1 << 20, None) == 6
+    assert lib.ptqtp_gemv_batch(None, 5, None) == 1
+    assert lib.ptqtp_gemv_batch(fake, 0, None) == 2
+
+
 def test_status_strings_and_version(lib):
     assert lib.ptqtp_version() >= 100
     seen = set()
@@ -82,4 +109,7 @@ def test_argument_validation_without_launch(lib):
     assert lib.ptqtp_tune(b"gemv_waves", 8) == 0
     assert lib.ptqtp_tune(b"gemv_waves", 0) == 0
     assert lib.ptqtp_tune(b"gemv_rows", 3) == 2
+    assert lib.ptqtp_tune(b"stream_depth", 3) == 2
+    assert lib.ptqtp_tune(b"stream_waves", 17) == 2
+    assert lib.ptqtp_tune(b"stream_waves", 0) == 0
     assert lib.ptqtp_tune(b"nonsense", 1) == 2

@@ -119,6 +119,61 @@ def test_gemv_launch_shapes(ptq, waves, rows):
         ptq.ptqtp_tune("gemv_rows", 0)
 
 
+@pytest.mark.parametrize("waves,depth", [(1, 1), (4, 4), (8, 2), (16, 1), (3, 4), (16, 4)])
+def test_gemv_item_kernel_launch_shapes(ptq, waves, depth):
+    # waves per item x records in flight: all give the same layer, including K/256 < waves,
+    # an odd number of groups (K = 640) and a ragged last row tile
+    try:
+        ptq.ptqtp_tune("stream_waves", waves)
+        ptq.ptqtp_tune("stream_depth", depth)
+        for N, K in [(200, 2304), (7, 640), (1000, 1024), (33, 14336)]:
+            lin = workloads.make_linear(N, K, 54, N)
+            x = workloads.make_x(1, K, 54, N)
+            check(ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), N, K), lin, x)
+    finally:
+        ptq.ptqtp_tune("stream_waves", 0)
+        ptq.ptqtp_tune("stream_depth", 0)
+
+
+def test_gemv_tiled_kernel_still_right(ptq):
+    try:
+        ptq.ptqtp_tune("gemv_stream", 0)
+        for N, K in [(200, 2304), (7, 640), (1000, 4096)]:
+            lin = workloads.make_linear(N, K, 54, N)
+            x = workloads.make_x(1, K, 54, N)
+            check(ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), N, K), lin, x)
+    finally:
+        ptq.ptqtp_tune("gemv_stream", -1)
+
+
+def test_gemv_batch_matches_oracle_and_single_calls(ptq):
+    # one launch over linears of different shapes, each with its own x
+    shapes = [(200, 2304), (7, 640), (1024, 1024), (33, 14336), (16, 128), (528, 4096)] * 2
+    lins, xs, entries, singles = [], [], [], []
+    for i, (N, K) in enumerate(shapes):
+        lin = workloads.make_linear(N, K, 64, i)
+        x = workloads.make_x(1, K, 64, i)
+        packed = pack(ptq, lin)
+        xd = dev(x).reshape(-1)
+        y = torch.full((1, N), float("nan"), dtype=torch.float32, device="cuda:0")
+        lins.append(lin); xs.append(x)
+        entries.append((packed, xd, y, N, K))
+        singles.append(ptq.ptqtp_gemv(packed, xd, N, K))
+    plan = ptq.ptqtp_gemv_batch_plan(entries)
+    assert plan.items == sum((N + 15) // 16 for N, _ in shapes)
+    for rep in range(3):
+        ptq.ptqtp_gemv_batch(plan)
+    for lin, x, ent, y1 in zip(lins, xs, entries, singles):
+        check(ent[2], lin, x)
+        assert torch.equal(ent[2], y1)          # same kernel, same reduction order as the single call
+    # fp16 outputs
+    ents16 = [(e[0], e[1], torch.empty((1, e[3]), dtype=torch.float16, device="cuda:0"), e[3], e[4]) for e in entries]
+    plan16 = ptq.ptqtp_gemv_batch_plan(ents16, y_dtype=ptq.PTQTP_F16)
+    ptq.ptqtp_gemv_batch(plan16)
+    for lin, x, ent in zip(lins, xs, ents16):
+        check(ent[2], lin, x, tight=TIGHT_F16)
+
+
 def test_gemv_unit_vectors_exact(ptq):
     # x = e_j returns column j of W^ = a1 T1 + a2 T2; with a2/a1 in [0.1, 0.5] the sum is exact in fp32
     N, K = 80, 768
