@@ -3,7 +3,7 @@
 // y[m,n] = sum_g alpha1[n,g] * (T1[n,g,:] . x[m,g,:]) + alpha2[n,g] * (T2[n,g,:] . x[m,g,:])
 // (paper, Eq. 1-2 with the group-wise scales of paragraph "Batch Processing").
 //
-// Device layout of the packed blob (layout id 1)
+// Device layout of the packed blob (layout id 2)
 // ----------------------------------------------
 //   [ 256-byte header ][ record(rt=0,ks=0) ][ record(rt=0,ks=1) ] ... [ record(rt=RT-1,ks=KS-1) ]
 //   rt = 16-row tile (RT = ceil(N/16)), ks = 256-column step (KS = ceil(K/256)) = two scale groups.
@@ -11,20 +11,22 @@
 //     bytes    0..1023  plane 1, 64 lanes x 16 B   (one global_load_dwordx4 per wave)
 //     bytes 1024..2047  plane 2, same shape
 //     bytes 2048..2175  scales: row nl (0..15) -> {a1[g0], a1[g1], a2[g0], a2[g1]} fp16
-//   Lane l = q*16 + nl holds 64 trits of row rt*16+nl: word i (0..3), 16-bit half h (0..1),
-//   2-bit field f (0..7) is column
-//       k = ks*256 + (f/4)*128 + q*32 + (f%4)*8 + i*2 + h
-//   and sits at bits [16h+15-2f : 16h+14-2f] as (sign, nonzero): 0 -> 00, +1 -> 01, -1 -> 11.
-//   Decoding field f of all four words is `(w << 2f) & 0xC000C000`: the two halves become the
-//   fp16 values {0, +2.0, -2.0}; the eight halves of a lane are exactly one lane's share of the
-//   32-deep K dimension of v_mfma_f32_16x16x32_f16.  Fields 0..3 belong to scale group g0 and
-//   4..7 to g1, so four MFMAs accumulate one (row, group) trit sum for 16 rows x 16 tokens.
+//   Lane l = q*16 + nl holds 64 trits of row rt*16+nl in four 32-bit words.  Word i (0..3),
+//   nibble j (0..7) holds two trits, A in bits (3,1) and B in bits (2,0) of the nibble, each as
+//   (sign, nonzero): 0 -> 00, +1 -> 01, -1 -> 11.  With f = 2i for A and f = 2i+1 for B the trit
+//   is column
+//       k = ks*256 + (f/4)*128 + q*32 + (f%4)*8 + j
+//   `w & 0xAAAAAAAA` (A) and `(w << 1) & 0xAAAAAAAA` (B) are then eight FP4 (E2M1) numbers in
+//   {0, +1, -1} (sign in bit 3, exponent LSB in bit 1), which v_cvt_scalef32_pk_f16_fp4 expands
+//   two at a time into fp16: 11 VALU operations per 16 trits.  The eight fp16 values of a field
+//   are exactly one lane's share of the 32-deep K dimension of v_mfma_f32_16x16x32_f16.  Fields
+//   0..3 (words 0,1) belong to scale group g0 and 4..7 (words 2,3) to g1, so four MFMAs
+//   accumulate one (row, group) trit sum for 16 rows x 16 tokens.
 //
 // Why MFMA for a GEMV: "multiplication-free" (Sec. "Inference Efficiency") is a statement about
-// the mathematics.  On CDNA4 a product by +-2.0/0 in the matrix pipe is exact and is the cheapest
-// way to add: it leaves the vector ALU only the 1 shift + 1 and per trit pair, which is what
-// keeps the kernel under the HBM roof instead of the VALU roof.  The factor 2 is removed exactly
-// by a final multiply with 0.5.
+// the mathematics.  On CDNA4 a product by +-1/0 in the matrix pipe is exact and is the cheapest
+// way to add: it leaves the vector ALU only the expansion of the 2-bit codes, which is what
+// keeps the kernel under the HBM roof instead of the VALU roof.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
@@ -39,9 +41,8 @@ constexpr int kStepK = 256;
 constexpr int kPlaneBytes = 1024;
 constexpr int kRecordBytes = 2 * kPlaneBytes + 128;
 constexpr uint64_t kMagic = 0x3130765054515450ull;  // "PTQTPv01" little-endian
-constexpr uint32_t kLayoutId = 1;
+constexpr uint32_t kLayoutId = 2;
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
@@ -102,14 +103,16 @@ pack_kernel(const int8_t *__restrict__ T1, const int8_t *__restrict__ T2,
         bool bad = false;
         if (n < N) {
 #pragma unroll
-            for (int f = 0; f < 8; ++f) {
-                const int64_t k = ks * kStepK + (f >> 2) * 128 + q * 32 + (f & 3) * 8 + i * 2;
+            for (int par = 0; par < 2; ++par) {
+                const int f = 2 * i + par;
+                const int64_t k = ks * kStepK + (f >> 2) * 128 + q * 32 + (f & 3) * 8;
                 if (k < K) {
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        int v = T[n * K + k + h];
+                    for (int j = 0; j < 8; ++j) {
+                        int v = T[n * K + k + j];
                         if (v < -1 || v > 1) { bad = true; v = 0; }
-                        word |= (static_cast<uint32_t>(v) & 3u) << (16 * h + 14 - 2 * f);
+                        const uint32_t code = static_cast<uint32_t>(v) & 3u;       // (sign, nonzero)
+                        word |= ((code >> 1) << (4 * j + 3 - par)) | ((code & 1u) << (4 * j + 1 - par));
                     }
                 }
             }
@@ -138,16 +141,16 @@ unpack_trits_kernel(const uint8_t *__restrict__ blob, int8_t *__restrict__ T1, i
     const int64_t rt = n / kTileRows, ks = k / kStepK;
     const int nl = static_cast<int>(n % kTileRows);
     const int kk = static_cast<int>(k % kStepK);
-    const int g2 = kk >> 7, q = (kk >> 5) & 3, fm = (kk >> 3) & 3, i = (kk >> 1) & 3, h = kk & 1;
-    const int f = g2 * 4 + fm, lane = q * 16 + nl;
+    const int g2 = kk >> 7, q = (kk >> 5) & 3, fm = (kk >> 3) & 3, j = kk & 7;
+    const int f = g2 * 4 + fm, lane = q * 16 + nl, i = f >> 1, par = f & 1;
     const uint8_t *rec = blob + kHeaderBytes + (rt * KS + ks) * kRecordBytes;
 #pragma unroll
     for (int plane = 0; plane < 2; ++plane) {
         int8_t *T = plane ? T2 : T1;
         if (!T) continue;
         const uint32_t w = reinterpret_cast<const uint32_t *>(rec + plane * kPlaneBytes)[lane * 4 + i];
-        const uint32_t code = (w >> (16 * h + 14 - 2 * f)) & 3u;
-        T[idx] = static_cast<int8_t>(code == 3u ? -1 : static_cast<int>(code & 1u));
+        const uint32_t sign = (w >> (4 * j + 3 - par)) & 1u, nz = (w >> (4 * j + 1 - par)) & 1u;
+        T[idx] = static_cast<int8_t>(nz ? (sign ? -1 : 1) : 0);
     }
 }
 
@@ -173,15 +176,18 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t bits16) {
     return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(bits16)));
 }
 
-// Field f of four packed words -> eight fp16 values in {0, +2, -2}: one lane's MFMA B operand.
+// Field F of four packed words -> eight fp16 values in {0, +1, -1}: one lane's MFMA B operand.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 template <int F>
 __device__ __forceinline__ half8 decode_field(uintx4 w) {
-    uintx4 b;
-    b.x = (w.x << (2 * F)) & 0xC000C000u;
-    b.y = (w.y << (2 * F)) & 0xC000C000u;
-    b.z = (w.z << (2 * F)) & 0xC000C000u;
-    b.w = (w.w << (2 * F)) & 0xC000C000u;
-    return __builtin_bit_cast(half8, b);
+    const uint32_t word = (F >> 1) == 0 ? w.x : (F >> 1) == 1 ? w.y : (F >> 1) == 2 ? w.z : w.w;
+    const uint32_t fp4 = ((F & 1) ? (word << 1) : word) & 0xAAAAAAAAu;
+    const half2v h0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 0);
+    const half2v h1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 1);
+    const half2v h2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 2);
+    const half2v h3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 3);
+    return half8{h0.x, h0.y, h1.x, h1.y, h2.x, h2.y, h3.x, h3.y};
 }
 
 // One (plane, 128-column group): four MFMAs of 16 tokens x 16 rows x 32 columns each.
@@ -310,7 +316,6 @@ gemv_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x,
     for (int o = threadIdx.x; o < OUT; o += blockDim.x) {
         float s = 0.f;
         for (int ww = 0; ww < W; ++ww) s += red[ww * OUT + o];
-        s *= 0.5f;   // trits were decoded as +-2.0
         int r, m;
         const int on = o & 15;
         if (SINGLE) { r = o >> 4; m = 0; }
@@ -470,7 +475,6 @@ gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int si
     if (threadIdx.x < 16) {
         float s = 0.f;
         for (int ww = 0; ww < W; ++ww) s += red[ww][threadIdx.x];
-        s *= 0.5f;   // trits were decoded as +-2.0
         const int n = rt * kTileRows + threadIdx.x;
         if (n < N) {
             if (y_f16) reinterpret_cast<_Float16 *>(dp->y)[n] = static_cast<_Float16>(s);
@@ -487,7 +491,7 @@ hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_
                         hipStream_t stream)
 {
     const int W = g_tune_stream_waves > 0 ? g_tune_stream_waves : 4;
-    const int S = g_tune_stream_depth > 0 ? g_tune_stream_depth : 4;
+    const int S = g_tune_stream_depth > 0 ? g_tune_stream_depth : 2;
     const dim3 grid(static_cast<unsigned>(total_items)), block(W * 64);
     if (S >= 4) hipLaunchKernelGGL((gemv_items_kernel<PLAN, 4>), grid, block, 0, stream, plan, single, y_f16);
     else if (S >= 2) hipLaunchKernelGGL((gemv_items_kernel<PLAN, 2>), grid, block, 0, stream, plan, single, y_f16);
