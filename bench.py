@@ -116,6 +116,9 @@ def main() -> int:
                     help="batch: one ptqtp_gemv_batch launch per step; graph: 7*layers ptqtp_gemv launches "
                          "replayed as one hipGraph; eager: the same launches issued call by call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run 5 plain 1 GiB device copies (known HBM traffic) and exit: the reference that "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
     ap.add_argument("--per-shape", action="store_true", help="also time every shape on its own (hot and cold)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -134,6 +137,16 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     names = workloads.LINEAR_ORDER
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"bytes_read_per_copy": 1 << 30, "bytes_written_per_copy": 1 << 30,
+                                             "copies": 5}}), flush=True)
+        return 0
 
     blobs, xs, ys, jobs, dims, layer0 = build_stack(ptq, torch, workloads, args.layers, dev)
     bytes_step = sum(algorithmic_bytes(n, k) for n, k in dims)
@@ -168,7 +181,8 @@ def main() -> int:
         "pct_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "achieved": round(bytes_launch / (launch_us * 1e-6) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(bytes_launch / (launch_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(bytes_launch / (launch_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": recorded_traffic(args.mode, args.layers),
                      "kernel": "gemv_items_kernel", "avg_launch_us": round(launch_us, 3),
                      "bytes_per_launch": round(bytes_launch)},
     }
@@ -177,6 +191,19 @@ def main() -> int:
         out["cpu_baseline"] = cpu_baseline(layer0, names)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def recorded_traffic(mode: str, layers: int):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by the plain-copy calibration); taken from the committed profile summary, None if absent or if
+    this run's launch shape is not the profiled one."""
+    path = os.path.join(ROOT, "profiles", "gemv_items_batch_8b_stack.txt")
+    if mode != "batch" or layers != 32 or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return int(float(line.split(":")[1].split()[0]))
+    return None
 
 
 def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, reps=200):
