@@ -109,8 +109,8 @@ def time_steps(torch, step, steps, warmup, stream):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--mode", choices=["batch", "graph", "eager"], default="batch",
                     help="batch: one ptqtp_gemv_batch launch per step; graph: 7*layers ptqtp_gemv launches "

@@ -164,7 +164,8 @@ ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream);
  * workgroup, 1..16), "gemv_rows" (16-row tiles per workgroup, 1, 2 or 4),
  * "gemv_stream" (batch 1: 1 = item kernel, 0 = tiled kernel, -1 = default),
  * "stream_waves" (waves per item, 1..16), "stream_depth" (records in flight per
- * wave: 1, 2 or 4);
+ * wave: 1, 2 or 4), "small_items" (batch > 1: 1 = item kernel, 0 = tiled kernel,
+ * -1 = default), "small_waves" (waves per item for batch > 1, 1..8);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
  * unknown key or out-of-range value.  Not thread-safe.
  */

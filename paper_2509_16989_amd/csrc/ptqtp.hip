@@ -3,7 +3,7 @@
 // y[m,n] = sum_g alpha1[n,g] * (T1[n,g,:] . x[m,g,:]) + alpha2[n,g] * (T2[n,g,:] . x[m,g,:])
 // (paper, Eq. 1-2 with the group-wise scales of paragraph "Batch Processing").
 //
-// Device layout of the packed blob (layout id 2)
+// Device layout of the packed blob (layout id 3)
 // ----------------------------------------------
 //   [ 256-byte header ][ record(rt=0,ks=0) ][ record(rt=0,ks=1) ] ... [ record(rt=RT-1,ks=KS-1) ]
 //   rt = 16-row tile (RT = ceil(N/16)), ks = 256-column step (KS = ceil(K/256)) = two scale groups.
@@ -15,7 +15,8 @@
 //   nibble j (0..7) holds two trits, A in bits (3,1) and B in bits (2,0) of the nibble, each as
 //   (sign, nonzero): 0 -> 00, +1 -> 01, -1 -> 11.  With f = 2i for A and f = 2i+1 for B the trit
 //   is column
-//       k = ks*256 + (f/4)*128 + q*32 + (f%4)*8 + j
+//       k = ks*256 + (f/4)*128 + (f%4)*32 + q*8 + j
+//   (the four quarter-lanes q of a row read 64 contiguous bytes of x per field)
 //   `w & 0xAAAAAAAA` (A) and `(w << 1) & 0xAAAAAAAA` (B) are then eight FP4 (E2M1) numbers in
 //   {0, +1, -1} (sign in bit 3, exponent LSB in bit 1), which v_cvt_scalef32_pk_f16_fp4 expands
 //   two at a time into fp16: 11 VALU operations per 16 trits.  The eight fp16 values of a field
@@ -41,7 +42,7 @@ constexpr int kStepK = 256;
 constexpr int kPlaneBytes = 1024;
 constexpr int kRecordBytes = 2 * kPlaneBytes + 128;
 constexpr uint64_t kMagic = 0x3130765054515450ull;  // "PTQTPv01" little-endian
-constexpr uint32_t kLayoutId = 2;
+constexpr uint32_t kLayoutId = 3;
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
@@ -105,7 +106,7 @@ pack_kernel(const int8_t *__restrict__ T1, const int8_t *__restrict__ T2,
 #pragma unroll
             for (int par = 0; par < 2; ++par) {
                 const int f = 2 * i + par;
-                const int64_t k = ks * kStepK + (f >> 2) * 128 + q * 32 + (f & 3) * 8;
+                const int64_t k = ks * kStepK + (f >> 2) * 128 + (f & 3) * 32 + q * 8;
                 if (k < K) {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
@@ -141,7 +142,7 @@ unpack_trits_kernel(const uint8_t *__restrict__ blob, int8_t *__restrict__ T1, i
     const int64_t rt = n / kTileRows, ks = k / kStepK;
     const int nl = static_cast<int>(n % kTileRows);
     const int kk = static_cast<int>(k % kStepK);
-    const int g2 = kk >> 7, q = (kk >> 5) & 3, fm = (kk >> 3) & 3, j = kk & 7;
+    const int g2 = kk >> 7, fm = (kk >> 5) & 3, q = (kk >> 3) & 3, j = kk & 7;
     const int f = g2 * 4 + fm, lane = q * 16 + nl, i = f >> 1, par = f & 1;
     const uint8_t *rec = blob + kHeaderBytes + (rt * KS + ks) * kRecordBytes;
 #pragma unroll
@@ -262,7 +263,7 @@ gemv_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x,
             const bool live = SINGLE ? (nl == 0) : (m < M);
 #pragma unroll
             for (int f = 0; f < 8; ++f) {
-                const int k0 = ks * kStepK + (f >> 2) * 128 + q * 32 + (f & 3) * 8;
+                const int k0 = ks * kStepK + (f >> 2) * 128 + (f & 3) * 32 + q * 8;
                 xa[mt][f] = uintx4{0, 0, 0, 0};
                 if (live && k0 < K)
                     xa[mt][f] = *reinterpret_cast<const uintx4 *>(x + static_cast<size_t>(m) * K + k0);
@@ -392,6 +393,12 @@ template <class T>
 __device__ __forceinline__ T load_global(const void *p) {
     return *(const __attribute__((address_space(1))) T *)(p);
 }
+// Same, marked non-temporal: the packed records are read exactly once per call and must not
+// push the activations (re-read by every workgroup) out of L2.
+template <class T>
+__device__ __forceinline__ T load_stream(const void *p) {
+    return __builtin_nontemporal_load((const __attribute__((address_space(1))) T *)(p));
+}
 
 struct StepRegs {             // one record + its activation slice
     uintx4 p1, p2;
@@ -423,12 +430,13 @@ gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int si
     const int K = dp->K, KS = dp->KS, N = dp->N;
     const int rt = item - dp->first_item;
     const uint8_t *rec0 = dp->records + static_cast<size_t>(rt) * KS * kRecordBytes;
+    const int rot = (rt * 5) % KS;
     const uint16_t *x = dp->x;
 
     uintx4 xa[1][8];
 #pragma unroll
     for (int f = 0; f < 8; ++f) xa[0][f] = uintx4{0, 0, 0, 0};   // lanes of tokens 1..15 stay zero
-    const char *xs_rd = reinterpret_cast<const char *>(&xs[w][0]) + q * 64;
+    const char *xs_rd = reinterpret_cast<const char *>(&xs[w][0]) + q * 16;
     float yacc = 0.f;
 
     for (int ks0 = w; ks0 < KS; ks0 += S * W) {
@@ -438,11 +446,12 @@ gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int si
 #pragma unroll
         for (int i = 0; i < S; ++i) {
             const int ks = ks0 + i * W;
-            const int kse = ks < KS ? ks : ks0;
+            int kse = (ks < KS ? ks : ks0) + rot;       // rotated start: neighbours hit different x lines
+            kse = kse >= KS ? kse - KS : kse;
             const uint8_t *rec = rec0 + static_cast<size_t>(kse) * kRecordBytes;
-            r[i].p1 = load_global<uintx4>(rec + lane * 16);
-            r[i].p2 = load_global<uintx4>(rec + kPlaneBytes + lane * 16);
-            r[i].sc = load_global<uintx2>(rec + 2 * kPlaneBytes + nl * 8);
+            r[i].p1 = load_stream<uintx4>(rec + lane * 16);
+            r[i].p2 = load_stream<uintx4>(rec + kPlaneBytes + lane * 16);
+            r[i].sc = load_stream<uintx2>(rec + 2 * kPlaneBytes + nl * 8);
             int k = kse * kStepK + lane * 4;
             k = k < K ? k : 0;                                   // odd number of groups: tail lanes
             r[i].xr = load_global<uintx2>(x + k);
@@ -452,12 +461,14 @@ gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int si
             const int ks = ks0 + i * W;
             if (ks < KS) {
                 uintx2 xr = r[i].xr;
-                if (ks * kStepK + lane * 4 >= K) xr = uintx2{0, 0};
+                int kr = ks + rot;
+                kr = kr >= KS ? kr - KS : kr;
+                if (kr * kStepK + lane * 4 >= K) xr = uintx2{0, 0};
                 xs[w][lane] = xr;                                // wave-private bounce: no barrier
                 if (nl == 0) {
 #pragma unroll
                     for (int f = 0; f < 8; ++f)
-                        xa[0][f] = *reinterpret_cast<const uintx4 *>(xs_rd + (f >> 2) * 256 + (f & 3) * 16);
+                        xa[0][f] = *reinterpret_cast<const uintx4 *>(xs_rd + (f >> 2) * 256 + (f & 3) * 64);
                 }
                 const float a1g0 = half_bits_to_float(r[i].sc.x & 0xffffu), a1g1 = half_bits_to_float(r[i].sc.x >> 16);
                 const float a2g0 = half_bits_to_float(r[i].sc.y & 0xffffu), a2g1 = half_bits_to_float(r[i].sc.y >> 16);
@@ -496,6 +507,142 @@ hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_
     if (S >= 4) hipLaunchKernelGGL((gemv_items_kernel<PLAN, 4>), grid, block, 0, stream, plan, single, y_f16);
     else if (S >= 2) hipLaunchKernelGGL((gemv_items_kernel<PLAN, 2>), grid, block, 0, stream, plan, single, y_f16);
     else hipLaunchKernelGGL((gemv_items_kernel<PLAN, 1>), grid, block, 0, stream, plan, single, y_f16);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// small-batch kernel (2 <= M <= 64): item = R consecutive 16-row tiles of one linear
+// ------------------------------------------------------------------------------------------
+// Same record stream as the batch-1 kernel; each decoded field feeds MT = ceil(M/16) MFMAs.
+// The activations of a step are loaded straight into the MFMA A-operand layout from L2
+// (lane (token nl, quarter q) needs 8 consecutive fp16 per field) and shared by the item's R
+// row tiles.  Lanes of tokens >= M load the last real token again: their rows of D are
+// garbage that is never stored (rows of A only influence the same rows of D).
+template <int MT, int R, int S>
+__global__ void __launch_bounds__(512)
+gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
+                  int M, int N, int K, int RT, int KS, int y_f16)
+{
+    extern __shared__ float red[];                     // [W][R][MT][16 tokens][16 rows]
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int W = blockDim.x >> 6;
+    const int nl = lane & 15, q = lane >> 4;
+    const int rt0 = blockIdx.x * R;
+    const int rot = (blockIdx.x * 5) % KS;
+
+    float yacc[R][MT][4];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) yacc[r][mt][j] = 0.f;
+
+    const uint16_t *xrow[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        int m = mt * 16 + nl;
+        m = m < M ? m : M - 1;
+        xrow[mt] = x + static_cast<size_t>(m) * K + q * 8;
+    }
+
+    for (int ks0 = w; ks0 < KS; ks0 += S * W) {
+        uintx4 p1[S][R], p2[S][R];
+        uintx2 sc[S][R];
+        uintx4 xa[S][MT][8];
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            const int ks = ks0 + i * W;
+            int kse = (ks < KS ? ks : ks0) + rot;        // past the end: re-read, result unused
+            kse = kse >= KS ? kse - KS : kse;              // rotated start: neighbours hit different x lines
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int rt = rt0 + r < RT ? rt0 + r : rt0;
+                const uint8_t *rec = records + (static_cast<size_t>(rt) * KS + kse) * kRecordBytes;
+                p1[i][r] = load_stream<uintx4>(rec + lane * 16);
+                p2[i][r] = load_stream<uintx4>(rec + kPlaneBytes + lane * 16);
+                sc[i][r] = load_stream<uintx2>(rec + 2 * kPlaneBytes + nl * 8);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int f = 0; f < 8; ++f) {
+                    int k0 = kse * kStepK + (f >> 2) * 128;
+                    k0 = k0 < K ? k0 : k0 - 128;         // padded half record: its trits are zero
+                    xa[i][mt][f] = load_global<uintx4>(xrow[mt] + k0 + (f & 3) * 32);
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            const int ks = ks0 + i * W;
+            if (ks < KS) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const float a1g0 = half_bits_to_float(sc[i][r].x & 0xffffu), a1g1 = half_bits_to_float(sc[i][r].x >> 16);
+                    const float a2g0 = half_bits_to_float(sc[i][r].y & 0xffffu), a2g1 = half_bits_to_float(sc[i][r].y >> 16);
+                    floatx4 acc[MT];
+                    group_sum<MT, 0>(xa[i], p1[i][r], acc);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) yacc[r][mt][j] = fmaf(a1g0, acc[mt][j], yacc[r][mt][j]);
+                    group_sum<MT, 1>(xa[i], p1[i][r], acc);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) yacc[r][mt][j] = fmaf(a1g1, acc[mt][j], yacc[r][mt][j]);
+                    group_sum<MT, 0>(xa[i], p2[i][r], acc);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) yacc[r][mt][j] = fmaf(a2g0, acc[mt][j], yacc[r][mt][j]);
+                    group_sum<MT, 1>(xa[i], p2[i][r], acc);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) yacc[r][mt][j] = fmaf(a2g1, acc[mt][j], yacc[r][mt][j]);
+                }
+            }
+        }
+    }
+
+    constexpr int OUT = R * MT * 256;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                red[w * OUT + ((r * MT + mt) * 16 + 4 * q + j) * 16 + nl] = yacc[r][mt][j];
+    __syncthreads();
+    for (int o = threadIdx.x; o < OUT; o += blockDim.x) {
+        float s = 0.f;
+        for (int ww = 0; ww < W; ++ww) s += red[ww * OUT + o];
+        const int on = o & 15, t = o >> 4;
+        const int m = (t / 16 % MT) * 16 + (t & 15), r = t / (16 * MT);
+        const int n = (rt0 + r) * kTileRows + on;
+        if (m < M && rt0 + r < RT && n < N) {
+            const size_t off = static_cast<size_t>(m) * N + n;
+            if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(s);
+            else reinterpret_cast<float *>(y)[off] = s;
+        }
+    }
+}
+
+int g_tune_small_waves = 0, g_tune_small = -1;
+
+template <int MT, int R, int S>
+hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
+                             hipStream_t stream)
+{
+    int W = g_tune_small_waves > 0 ? g_tune_small_waves : 4;
+    if (W > 8) W = 8;
+    const int grid = static_cast<int>((s.RT + R - 1) / R);
+    const size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
+    hipLaunchKernelGGL((gemm_items_kernel<MT, R, S>), dim3(grid), dim3(W * 64), lds, stream, records, x, y, M,
+                       static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
+                       static_cast<int>(s.KS), y_f16);
     return hipGetLastError();
 }
 
@@ -548,6 +695,10 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
         if (R >= 4) e = launch_gemv<1, 4, true>(records, x, y, Mi, s, W, f16, stream);
         else if (R >= 2) e = launch_gemv<1, 2, true>(records, x, y, Mi, s, W, f16, stream);
         else e = launch_gemv<1, 1, true>(records, x, y, Mi, s, W, f16, stream);
+    } else if (g_tune_small != 0) {
+        if (M <= 16) e = launch_gemm_items<1, 1, 2>(records, x, y, Mi, s, f16, stream);
+        else if (M <= 32) e = launch_gemm_items<2, 1, 1>(records, x, y, Mi, s, f16, stream);
+        else e = launch_gemm_items<4, 1, 1>(records, x, y, Mi, s, f16, stream);
     } else if (M <= 16) {
         const int W = pick_waves(s.KS, 16);
         int R = g_tune_rows > 0 ? g_tune_rows : (s.RT >= 4096 ? 2 : 1);
@@ -732,6 +883,16 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!strcmp(key, "stream_waves")) {
         if (value < 0 || value > 16) return PTQTP_ERR_SHAPE;
         g_tune_stream_waves = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "small_waves")) {
+        if (value < 0 || value > 8) return PTQTP_ERR_SHAPE;
+        g_tune_small_waves = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "small_items")) {
+        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
+        g_tune_small = value;
         return PTQTP_OK;
     }
     if (!strcmp(key, "stream_depth")) {
