@@ -128,6 +128,17 @@ ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, in
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Any batch, 1 <= M <= PTQTP_GEMM_MAX_M: dispatches to the batch-1 kernel, the small-batch
+ * kernel, or -- above PTQTP_GEMM_SMALL_MAX_M tokens (prefill), where the layer is a dense
+ * contraction -- an MFMA tile that stages activations in LDS and feeds alpha*T (exact in
+ * fp16) to the matrix pipe.  Arguments as in ptqtp_gemm_small.
+ */
+#define PTQTP_GEMM_MAX_M 65536
+ptqtp_status ptqtp_gemm(const void *packed, const uint16_t *x, void *y, int32_t y_dtype,
+                        int64_t M, int64_t N, int64_t K, int32_t group,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Many independent batch-1 layers in ONE launch (fused q/k/v, gate/up, or a whole
  * stack of layers whose inputs are all known): the same sum as ptqtp_gemv for each
  * entry.  One launch covers every 16-row tile of every entry, so the HBM stream does
@@ -165,7 +176,8 @@ ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream);
  * "gemv_stream" (batch 1: 1 = item kernel, 0 = tiled kernel, -1 = default),
  * "stream_waves" (waves per item, 1..16), "stream_depth" (records in flight per
  * wave: 1, 2 or 4), "small_items" (batch > 1: 1 = item kernel, 0 = tiled kernel,
- * -1 = default), "small_waves" (waves per item for batch > 1, 1..8);
+ * -1 = default), "small_waves" (waves per item for batch > 1, 1..8), "tile"
+ * (1 = use the MFMA tile for every batch > 1, -1 = default);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
  * unknown key or out-of-range value.  Not thread-safe.
  */

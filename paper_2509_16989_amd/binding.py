@@ -53,6 +53,8 @@ def _load():
         lib.ptqtp_gemv.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
         lib.ptqtp_gemm_small.restype = i32
         lib.ptqtp_gemm_small.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
+        lib.ptqtp_gemm.restype = i32
+        lib.ptqtp_gemm.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
         lib.ptqtp_batch_plan_bytes.restype = sz
         lib.ptqtp_batch_plan_bytes.argtypes = [p, i32, i32]
         lib.ptqtp_batch_items.restype = i64
@@ -158,6 +160,13 @@ def ptqtp_gemm_small(packed, x, N: int, K: int, group: int = 128, y_dtype: int =
     if x.dim() != 2 or x.shape[1] != K:
         raise PtqtpError(2, "ptqtp_gemm_small")
     return _forward(_load().ptqtp_gemm_small, "ptqtp_gemm_small", packed, x, N, K, x.shape[0], group, y_dtype, out)
+
+
+def ptqtp_gemm(packed, x, N: int, K: int, group: int = 128, y_dtype: int = PTQTP_F32, out=None):
+    """y [M,N] for x fp16 [M,K], any M up to 65536 (prefill uses the MFMA tile)."""
+    if x.dim() != 2 or x.shape[1] != K:
+        raise PtqtpError(2, "ptqtp_gemm")
+    return _forward(_load().ptqtp_gemm, "ptqtp_gemm", packed, x, N, K, x.shape[0], group, y_dtype, out)
 
 
 class _Linear(ctypes.Structure):

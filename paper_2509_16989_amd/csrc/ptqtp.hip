@@ -499,10 +499,18 @@ int g_tune_stream_waves = 0, g_tune_stream_depth = 0;
 
 template <bool PLAN>
 hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_f16, int64_t total_items,
-                        hipStream_t stream)
+                        int64_t min_ks, hipStream_t stream)
 {
-    const int W = g_tune_stream_waves > 0 ? g_tune_stream_waves : 4;
-    const int S = g_tune_stream_depth > 0 ? g_tune_stream_depth : 2;
+    // A batched launch has thousands of items in flight: 4 waves x 2 records each is enough.  A single
+    // linear has few items, so more waves per item put the whole matrix in flight at once.
+    int W = 4, S = 2;
+    if (!PLAN) {
+        S = 1;
+        while (W < 16 && total_items * W * 2 <= 4096) W *= 2;
+        while (W > 1 && W > min_ks) W /= 2;
+    }
+    if (g_tune_stream_waves > 0) W = g_tune_stream_waves;
+    if (g_tune_stream_depth > 0) S = g_tune_stream_depth;
     const dim3 grid(static_cast<unsigned>(total_items)), block(W * 64);
     if (S >= 4) hipLaunchKernelGGL((gemv_items_kernel<PLAN, 4>), grid, block, 0, stream, plan, single, y_f16);
     else if (S >= 2) hipLaunchKernelGGL((gemv_items_kernel<PLAN, 2>), grid, block, 0, stream, plan, single, y_f16);
@@ -514,16 +522,21 @@ hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_
 // small-batch kernel (2 <= M <= 64): item = R consecutive 16-row tiles of one linear
 // ------------------------------------------------------------------------------------------
 // Same record stream as the batch-1 kernel; each decoded field feeds MT = ceil(M/16) MFMAs.
-// The activations of a step are loaded straight into the MFMA A-operand layout from L2
-// (lane (token nl, quarter q) needs 8 consecutive fp16 per field) and shared by the item's R
-// row tiles.  Lanes of tokens >= M load the last real token again: their rows of D are
-// garbage that is never stored (rows of A only influence the same rows of D).
+// Activations: a wave fetches the 16 tokens x 256 columns of its step with coalesced loads (four
+// neighbouring lanes read 64 contiguous bytes of one token), then turns them into the MFMA
+// A-operand layout (lane = token + 16*quarter) with one ds_write_b128 / ds_read_b128 pair per
+// field through a 1280-byte wave-private LDS slot -- LDS operations of a wave execute in order,
+// so the slot needs no barrier and can be reused immediately.  Lanes of tokens >= M load the
+// last real token again: their rows of D are garbage that is never stored (rows of A only
+// influence the same rows of D).
+constexpr int kBounceBytes = 1280;   // 4 quarters x 320 B: conflict-free for the write and the read
+
 template <int MT, int R, int S>
 __global__ void __launch_bounds__(512)
 gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
                   int M, int N, int K, int RT, int KS, int y_f16)
 {
-    extern __shared__ float red[];                     // [W][R][MT][16 tokens][16 rows]
+    extern __shared__ float red[];                     // [W][R][MT][16 tokens][16 rows]; first used as bounce slots
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int W = blockDim.x >> 6;
@@ -539,13 +552,18 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
 #pragma unroll
             for (int j = 0; j < 4; ++j) yacc[r][mt][j] = 0.f;
 
+    // loader role of this lane: token row lr, 16-byte chunk lc of every 64-byte field segment
+    const int lr = lane >> 2, lc = lane & 3;
     const uint16_t *xrow[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        int m = mt * 16 + nl;
+        int m = mt * 16 + lr;
         m = m < M ? m : M - 1;
-        xrow[mt] = x + static_cast<size_t>(m) * K + q * 8;
+        xrow[mt] = x + static_cast<size_t>(m) * K + lc * 8;
     }
+    char *slot = reinterpret_cast<char *>(red) + w * kBounceBytes;
+    char *slot_wr = slot + lc * 320 + lr * 16;          // where the loader puts (token lr, quarter lc)
+    const char *slot_rd = slot + q * 320 + nl * 16;     // where the MFMA lane (token nl, quarter q) finds it
 
     for (int ks0 = w; ks0 < KS; ks0 += S * W) {
         uintx4 p1[S][R], p2[S][R];
@@ -578,6 +596,13 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
             const int ks = ks0 + i * W;
             if (ks < KS) {
 #pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int f = 0; f < 8; ++f) {
+                        *reinterpret_cast<uintx4 *>(slot_wr) = xa[i][mt][f];
+                        xa[i][mt][f] = *reinterpret_cast<const uintx4 *>(slot_rd);
+                    }
+#pragma unroll
                 for (int r = 0; r < R; ++r) {
                     const float a1g0 = half_bits_to_float(sc[i][r].x & 0xffffu), a1g1 = half_bits_to_float(sc[i][r].x >> 16);
                     const float a2g0 = half_bits_to_float(sc[i][r].y & 0xffffu), a2g1 = half_bits_to_float(sc[i][r].y >> 16);
@@ -608,6 +633,7 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
     }
 
     constexpr int OUT = R * MT * 256;
+    __syncthreads();                                   // bounce slots are dead: the space becomes `red`
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -630,7 +656,193 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
     }
 }
 
-int g_tune_small_waves = 0, g_tune_small = -1;
+// ------------------------------------------------------------------------------------------
+// MFMA tile for large batches / prefill: here the path is a dense contraction
+// ------------------------------------------------------------------------------------------
+// Workgroup = 4 waves, each owning 4 row tiles x 4 token tiles (64 rows x 64 tokens, 16 MFMA
+// accumulators).  WGM waves sit side by side along the tokens, 4/WGM along the rows.  Per scale
+// group (128 columns) the workgroup stages its tokens' activations in LDS (coalesced loads,
+// padded rows, double-buffered, one barrier per group); every wave expands the trits of its own
+// four row tiles in registers and multiplies them by the group scale -- alpha * {0,+-1} is exact
+// in fp16, so alpha1*T1 and alpha2*T2 enter the matrix pipe directly and both planes share one
+// fp32 accumulator -- then issues 32 MFMAs per 32-column field against 4 LDS operand reads.
+// Workgroups are numbered so that all token blocks of a row block run on the same XCD and
+// share its L2 copy of the packed rows.
+constexpr int kTileXStride = 272;                    // bytes per token row of the LDS x tile (128 fp16 + pad)
+
+__device__ __forceinline__ half8 decode8(uint32_t word, int parity) {
+    const uint32_t fp4 = (parity ? (word << 1) : word) & 0xAAAAAAAAu;
+    const half2v h0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 0);
+    const half2v h1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 1);
+    const half2v h2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 2);
+    const half2v h3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 3);
+    return half8{h0.x, h0.y, h1.x, h1.y, h2.x, h2.y, h3.x, h3.y};
+}
+
+template <int WGM>
+__global__ void __launch_bounds__(256)
+gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
+                 int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB)
+{
+    extern __shared__ char xt[];                     // [2][TM][kTileXStride]
+    constexpr int WGN = 4 / WGM, TM = 64 * WGM, NRT = 4 * WGN;   // tokens, row tiles per workgroup
+    constexpr int XL = TM / 16;                      // 16-byte x loads per thread per group
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nl = lane & 15, q = lane >> 4;
+    const int wm = w % WGM, wn = w / WGM;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int nb = (slot / MB) * 8 + xcd, mb = slot % MB;
+    if (nb >= NB) return;                            // whole workgroup, before any barrier
+    const int m0 = mb * TM;
+    const int rt_base = nb * NRT + wn * 4;
+    const int NG = K / 128;
+
+    // staging role: thread t loads token row (t/16 + 16*j), 16-byte chunk t%16 of the group's 256 bytes
+    const int srow = threadIdx.x >> 4, schunk = threadIdx.x & 15;
+    const uint16_t *xsrc[XL];
+#pragma unroll
+    for (int j = 0; j < XL; ++j) {
+        int m = m0 + srow + 16 * j;
+        m = m < M ? m : M - 1;                       // rows past M: duplicates, never stored
+        xsrc[j] = x + static_cast<size_t>(m) * K + schunk * 8;
+    }
+    char *xdst = xt + srow * kTileXStride + schunk * 16;
+    const char *xop = xt + (wm * 64 + nl) * kTileXStride + q * 16;
+
+    const uint8_t *rec[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        int rt = rt_base + r;
+        rt = rt < RT ? rt : RT - 1;
+        rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes;
+    }
+
+    floatx4 acc[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    uintx4 stage[XL];
+    uintx4 p1[4], p2[4], np1[4], np2[4];
+    uintx2 sc[4], nsc[4];
+#pragma unroll
+    for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j]);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        p1[r] = load_global<uintx4>(rec[r] + lane * 16);
+        p2[r] = load_global<uintx4>(rec[r] + kPlaneBytes + lane * 16);
+        sc[r] = load_global<uintx2>(rec[r] + 2 * kPlaneBytes + nl * 8);
+        np1[r] = p1[r]; np2[r] = p2[r]; nsc[r] = sc[r];
+    }
+#pragma unroll
+    for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(xdst + j * 16 * kTileXStride) = stage[j];
+    __syncthreads();
+
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int g = ks * 2 + h;
+            if (g < NG) {
+                const bool more = g + 1 < NG;
+                if (more) {
+#pragma unroll
+                    for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j] + (g + 1) * 128);
+                }
+                if (h == 1 && ks + 1 < KS) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const uint8_t *nr = rec[r] + static_cast<size_t>(ks + 1) * kRecordBytes;
+                        np1[r] = load_global<uintx4>(nr + lane * 16);
+                        np2[r] = load_global<uintx4>(nr + kPlaneBytes + lane * 16);
+                        nsc[r] = load_global<uintx2>(nr + 2 * kPlaneBytes + nl * 8);
+                    }
+                }
+                const char *xb = xop + (g & 1) * (TM * kTileXStride);
+                half8 al1[4], al2[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].x >> 16) : (sc[r].x & 0xffffu)));
+                    const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].y >> 16) : (sc[r].y & 0xffffu)));
+                    al1[r] = half8{a1, a1, a1, a1, a1, a1, a1, a1};
+                    al2[r] = half8{a2, a2, a2, a2, a2, a2, a2, a2};
+                }
+#pragma unroll
+                for (int fm = 0; fm < 4; ++fm) {
+                    const int wi = 2 * h + (fm >> 1), par = fm & 1;
+                    half8 b1[4], b2[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        b1[r] = decode8(p1[r][wi], par) * al1[r];
+                        b2[r] = decode8(p2[r][wi], par) * al2[r];
+                    }
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) {
+                        const half8 a = __builtin_bit_cast(
+                            half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * kTileXStride + fm * 64));
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b1[r], acc[r][mt], 0, 0, 0);
+                            acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b2[r], acc[r][mt], 0, 0, 0);
+                        }
+                    }
+                }
+                if (more) {
+                    char *d = xdst + ((g + 1) & 1) * (TM * kTileXStride);
+#pragma unroll
+                    for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(d + j * 16 * kTileXStride) = stage[j];
+                }
+                __syncthreads();
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { p1[r] = np1[r]; p2[r] = np2[r]; sc[r] = nsc[r]; }
+    }
+
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int rt = rt_base + r;
+        const int n = rt * kTileRows + nl;
+        if (rt < RT && n < N) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int m = m0 + wm * 64 + mt * 16 + 4 * q + j;
+                    if (m < M) {
+                        const size_t off = static_cast<size_t>(m) * N + n;
+                        if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(acc[r][mt][j]);
+                        else reinterpret_cast<float *>(y)[off] = acc[r][mt][j];
+                    }
+                }
+        }
+    }
+}
+
+template <int WGM>
+hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
+                            hipStream_t stream)
+{
+    constexpr int TM = 64 * WGM, NRT = 4 * (4 / WGM);
+    const int MB = (M + TM - 1) / TM;
+    const int NB = static_cast<int>((s.RT + NRT - 1) / NRT);
+    const int64_t grid = static_cast<int64_t>((NB + 7) / 8) * 8 * MB;
+    const size_t lds = 2 * static_cast<size_t>(TM) * kTileXStride;
+    static bool configured = false;                  // raise the dynamic LDS limit once per process
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<WGM>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((gemm_tile_kernel<WGM>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
+                       y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
+                       static_cast<int>(s.KS), y_f16, MB, NB);
+    return hipGetLastError();
+}
+
+int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1;
 
 template <int MT, int R, int S>
 hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
@@ -639,7 +851,8 @@ hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y,
     int W = g_tune_small_waves > 0 ? g_tune_small_waves : 4;
     if (W > 8) W = 8;
     const int grid = static_cast<int>((s.RT + R - 1) / R);
-    const size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
+    size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
+    if (lds < static_cast<size_t>(W) * kBounceBytes) lds = static_cast<size_t>(W) * kBounceBytes;
     hipLaunchKernelGGL((gemm_items_kernel<MT, R, S>), dim3(grid), dim3(W * 64), lds, stream, records, x, y, M,
                        static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
                        static_cast<int>(s.KS), y_f16);
@@ -669,13 +882,13 @@ int pick_waves(int64_t KS, int wmax) {
 }
 
 ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M,
-                         int64_t N, int64_t K, int32_t group, void *stream_)
+                         int64_t N, int64_t K, int32_t group, void *stream_, int64_t max_m)
 {
     Shape s;
     ptqtp_status st;
     if (!packed || !x || !y) return PTQTP_ERR_NULL;
     if (!make_shape(M, N, K, group, &s, &st)) return st;
-    if (M > PTQTP_GEMM_SMALL_MAX_M) return PTQTP_ERR_SHAPE;
+    if (M > max_m) return PTQTP_ERR_SHAPE;
     if (y_dtype != PTQTP_F32 && y_dtype != PTQTP_F16) return PTQTP_ERR_DTYPE;
     if (!aligned(packed, 256) || !aligned(x, 16) || !aligned(y, y_dtype == PTQTP_F16 ? 2 : 4)) return PTQTP_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
@@ -688,13 +901,16 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
         d.N = static_cast<int32_t>(s.N); d.K = static_cast<int32_t>(s.K);
         d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
         d.first_item = 0; d.pad = 0;
-        e = launch_items<false>(nullptr, d, f16, s.RT, stream);
+        e = launch_items<false>(nullptr, d, f16, s.RT, s.KS, stream);
     } else if (M == 1) {
         const int W = pick_waves(s.KS, 16);
         int R = g_tune_rows > 0 ? g_tune_rows : (s.RT >= 4096 ? 2 : 1);
         if (R >= 4) e = launch_gemv<1, 4, true>(records, x, y, Mi, s, W, f16, stream);
         else if (R >= 2) e = launch_gemv<1, 2, true>(records, x, y, Mi, s, W, f16, stream);
         else e = launch_gemv<1, 1, true>(records, x, y, Mi, s, W, f16, stream);
+    } else if (M > PTQTP_GEMM_SMALL_MAX_M || g_tune_tile == 1) {
+        if (M <= 64) e = launch_gemm_tile<1>(records, x, y, Mi, s, f16, stream);
+        else e = launch_gemm_tile<2>(records, x, y, Mi, s, f16, stream);
     } else if (g_tune_small != 0) {
         if (M <= 16) e = launch_gemm_items<1, 1, 2>(records, x, y, Mi, s, f16, stream);
         else if (M <= 32) e = launch_gemm_items<2, 1, 1>(records, x, y, Mi, s, f16, stream);
@@ -789,13 +1005,19 @@ ptqtp_status ptqtp_gemv(const void *packed, const uint16_t *x, void *y, int32_t 
                         int64_t K, int32_t group, void *, size_t, void *stream)
 {
     if (M != 1) return PTQTP_ERR_SHAPE;
-    return run_forward(packed, x, y, y_dtype, M, N, K, group, stream);
+    return run_forward(packed, x, y, y_dtype, M, N, K, group, stream, 1);
 }
 
 ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M, int64_t N,
                               int64_t K, int32_t group, void *, size_t, void *stream)
 {
-    return run_forward(packed, x, y, y_dtype, M, N, K, group, stream);
+    return run_forward(packed, x, y, y_dtype, M, N, K, group, stream, PTQTP_GEMM_SMALL_MAX_M);
+}
+
+ptqtp_status ptqtp_gemm(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M, int64_t N,
+                        int64_t K, int32_t group, void *, size_t, void *stream)
+{
+    return run_forward(packed, x, y, y_dtype, M, N, K, group, stream, PTQTP_GEMM_MAX_M);
 }
 
 static ptqtp_status plan_items(const ptqtp_linear *linears, int32_t count, int32_t group, int64_t *total) {
@@ -868,7 +1090,7 @@ ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream_) {
     if (!aligned(plan, 256)) return PTQTP_ERR_ALIGN;
     if (items <= 0 || items > (1ll << 30)) return PTQTP_ERR_SHAPE;
     LinearDesc none = {};
-    const hipError_t e = launch_items<true>(static_cast<const PlanHeader *>(plan), none, 0, items,
+    const hipError_t e = launch_items<true>(static_cast<const PlanHeader *>(plan), none, 0, items, 16,
                                             static_cast<hipStream_t>(stream_));
     return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
@@ -883,6 +1105,11 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!strcmp(key, "stream_waves")) {
         if (value < 0 || value > 16) return PTQTP_ERR_SHAPE;
         g_tune_stream_waves = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "tile")) {
+        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
+        g_tune_tile = value;
         return PTQTP_OK;
     }
     if (!strcmp(key, "small_waves")) {

@@ -165,7 +165,17 @@ def test_gemv_batch_matches_oracle_and_single_calls(ptq):
         ptq.ptqtp_gemv_batch(plan)
     for lin, x, ent, y1 in zip(lins, xs, entries, singles):
         check(ent[2], lin, x)
-        assert torch.equal(ent[2], y1)          # same kernel, same reduction order as the single call
+        check(y1, lin, x)
+    # with the launch shape pinned, the batched launch gives the bits of the single calls
+    try:
+        ptq.ptqtp_tune("stream_waves", 4)
+        ptq.ptqtp_tune("stream_depth", 2)
+        ptq.ptqtp_gemv_batch(plan)
+        for ent in entries:
+            assert torch.equal(ent[2], ptq.ptqtp_gemv(ent[0], ent[1], ent[3], ent[4]))
+    finally:
+        ptq.ptqtp_tune("stream_waves", 0)
+        ptq.ptqtp_tune("stream_depth", 0)
     # fp16 outputs
     ents16 = [(e[0], e[1], torch.empty((1, e[3]), dtype=torch.float16, device="cuda:0"), e[3], e[4]) for e in entries]
     plan16 = ptq.ptqtp_gemv_batch_plan(ents16, y_dtype=ptq.PTQTP_F16)
@@ -277,6 +287,60 @@ def test_gemm_small_shapes(ptq, N, K, M):
     lin = workloads.make_linear(N, K, 61, N, K)
     x = workloads.make_x(M, K, 61, N, M)
     check(ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K), lin, x)
+
+
+# ---------------------------------------------------------------- MFMA tile (large batch / prefill)
+@pytest.mark.parametrize("N,K,M", [(528, 2048, 65), (528, 2048, 128), (200, 1024, 130), (1000, 640, 257),
+                                    (64, 128, 300), (2048, 4096, 512), (16, 384, 70), (4096, 256, 96)])
+def test_gemm_tile_shapes(ptq, N, K, M):
+    lin = workloads.make_linear(N, K, 70, N, K)
+    x = workloads.make_x(M, K, 70, N, M)
+    y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K)
+    check(y, lin, x, tight=3e-5)
+
+
+@pytest.mark.parametrize("M", [2, 16, 33, 64])
+def test_gemm_tile_forced_for_small_batches(ptq, M):
+    N, K = 328, 2304
+    lin = workloads.make_linear(N, K, 71)
+    x = workloads.make_x(M, K, 71, M)
+    try:
+        ptq.ptqtp_tune("tile", 1)
+        y = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K)
+        y16 = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K, y_dtype=ptq.PTQTP_F16)
+    finally:
+        ptq.ptqtp_tune("tile", -1)
+    check(y, lin, x, tight=3e-5)
+    check(y16, lin, x, tight=TIGHT_F16)
+
+
+def test_gemm_tile_integer_exact_and_general_scales(ptq):
+    N, K, M = 272, 1536, 144
+    lin, x = workloads.integer_exact_case(N, K, M, 72)
+    y_ref, _ = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+    y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K).cpu().numpy().astype(np.float64)
+    assert np.array_equal(y, y_ref)
+    r = np.random.default_rng(72)
+    lin = workloads.make_linear(N, K, 72, 1)
+    lin["a1"] = (r.standard_normal((N, K // 128)) * 3).astype(np.float16)
+    lin["a2"] = (r.standard_normal((N, K // 128)) * 1e-6).astype(np.float16)     # subnormal fp16 scales
+    x = workloads.make_x(M, K, 72, 1)
+    x[:, ::5] = (r.standard_normal(x[:, ::5].shape) * 2e-6).astype(np.float16)   # subnormal activations
+    check(ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K), lin, x, tight=3e-5)
+
+
+def test_gemm_tile_prefill_70b_sampled(ptq):
+    # prefill M = 2048 on a 70B-shaped k/v projection; sampled rows and tokens against the oracle
+    lin = workloads.linear_70b("k")
+    N, K, M = lin["N"], lin["K"], 2048
+    x = workloads.x_for("k", M, K, config=4)
+    y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K)
+    rows = np.unique(np.random.default_rng(4).integers(0, N, 48))
+    toks = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 2047], np.random.default_rng(5).integers(0, M, 24)]))
+    ref, B = oracle.forward(lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows], x[toks], threads=8)
+    got = y.cpu().numpy().astype(np.float64)[np.ix_(toks, rows)]
+    err = np.abs(got - ref)
+    assert np.all(err <= TOL * B) and np.all(err <= 3e-5 * B), f"{(err / B).max():.3e}"
 
 
 def test_gemm_small_rows_match_gemv(ptq):
