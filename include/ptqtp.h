@@ -129,9 +129,9 @@ ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, in
 
 /*
  * Any batch, 1 <= M <= PTQTP_GEMM_MAX_M: dispatches to the batch-1 kernel, the small-batch
- * kernel, or -- above PTQTP_GEMM_SMALL_MAX_M tokens (prefill), where the layer is a dense
- * contraction -- an MFMA tile that stages activations in LDS and feeds alpha*T (exact in
- * fp16) to the matrix pipe.  Arguments as in ptqtp_gemm_small.
+ * kernel (in chunks of 64 tokens up to 255), or -- from 256 tokens (prefill), where the
+ * layer is a dense contraction -- an MFMA tile that stages activations in LDS and feeds
+ * alpha*T (exact in fp16) to the matrix pipe.  Arguments as in ptqtp_gemm_small.
  */
 #define PTQTP_GEMM_MAX_M 65536
 ptqtp_status ptqtp_gemm(const void *packed, const uint16_t *x, void *y, int32_t y_dtype,

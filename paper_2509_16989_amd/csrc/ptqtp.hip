@@ -532,7 +532,7 @@ hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_
 constexpr int kBounceBytes = 1280;   // 4 quarters x 320 B: conflict-free for the write and the read
 
 template <int MT, int R, int S>
-__global__ void __launch_bounds__(512)
+__global__ void __launch_bounds__(MT * R >= 8 ? 256 : 512)
 gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
                   int M, int N, int K, int RT, int KS, int y_f16)
 {
@@ -659,13 +659,13 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
 // ------------------------------------------------------------------------------------------
 // MFMA tile for large batches / prefill: here the path is a dense contraction
 // ------------------------------------------------------------------------------------------
-// Workgroup = 4 waves, each owning 4 row tiles x 4 token tiles (64 rows x 64 tokens, 16 MFMA
-// accumulators).  WGM waves sit side by side along the tokens, 4/WGM along the rows.  Per scale
+// Workgroup = 4 waves along the rows, each owning 4 row tiles x MTW token tiles (64 rows x 64 or
+// 128 tokens, 16 or 32 MFMA accumulators).  Per scale
 // group (128 columns) the workgroup stages its tokens' activations in LDS (coalesced loads,
 // padded rows, double-buffered, one barrier per group); every wave expands the trits of its own
 // four row tiles in registers and multiplies them by the group scale -- alpha * {0,+-1} is exact
 // in fp16, so alpha1*T1 and alpha2*T2 enter the matrix pipe directly and both planes share one
-// fp32 accumulator -- then issues 32 MFMAs per 32-column field against 4 LDS operand reads.
+// fp32 accumulator -- then issues 8*MTW MFMAs per 32-column field against MTW LDS operand reads.
 // Workgroups are numbered so that all token blocks of a row block run on the same XCD and
 // share its L2 copy of the packed rows.
 constexpr int kTileXStride = 272;                    // bytes per token row of the LDS x tile (128 fp16 + pad)
@@ -679,23 +679,29 @@ __device__ __forceinline__ half8 decode8(uint32_t word, int parity) {
     return half8{h0.x, h0.y, h1.x, h1.y, h2.x, h2.y, h3.x, h3.y};
 }
 
-template <int WGM>
+struct TileRecs {               // the records of a wave's four row tiles for one 256-column step
+    uintx4 p1[4], p2[4];
+    uintx2 sc[4];
+};
+
+// MTW = token tiles per wave (4 or 8).  The four waves of a workgroup sit along the rows:
+// workgroup tile = 256 rows x 16*MTW tokens.
+template <int MTW>
 __global__ void __launch_bounds__(256)
 gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB)
 {
     extern __shared__ char xt[];                     // [2][TM][kTileXStride]
-    constexpr int WGN = 4 / WGM, TM = 64 * WGM, NRT = 4 * WGN;   // tokens, row tiles per workgroup
+    constexpr int TM = 16 * MTW, NRT = 16;           // tokens, row tiles per workgroup
     constexpr int XL = TM / 16;                      // 16-byte x loads per thread per group
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nl = lane & 15, q = lane >> 4;
-    const int wm = w % WGM, wn = w / WGM;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int nb = (slot / MB) * 8 + xcd, mb = slot % MB;
     if (nb >= NB) return;                            // whole workgroup, before any barrier
     const int m0 = mb * TM;
-    const int rt_base = nb * NRT + wn * 4;
+    const int rt_base = nb * NRT + w * 4;
     const int NG = K / 128;
 
     // staging role: thread t loads token row (t/16 + 16*j), 16-byte chunk t%16 of the group's 256 bytes
@@ -708,7 +714,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
         xsrc[j] = x + static_cast<size_t>(m) * K + schunk * 8;
     }
     char *xdst = xt + srow * kTileXStride + schunk * 16;
-    const char *xop = xt + (wm * 64 + nl) * kTileXStride + q * 16;
+    const char *xop = xt + nl * kTileXStride + q * 16;
 
     const uint8_t *rec[4];
 #pragma unroll
@@ -718,29 +724,34 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
         rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes;
     }
 
-    floatx4 acc[4][4];
+    floatx4 acc[4][MTW];
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < MTW; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    auto load_recs = [&](TileRecs &t, int ks) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint8_t *p = rec[r] + static_cast<size_t>(ks) * kRecordBytes;
+            t.p1[r] = load_global<uintx4>(p + lane * 16);
+            t.p2[r] = load_global<uintx4>(p + kPlaneBytes + lane * 16);
+            t.sc[r] = load_global<uintx2>(p + 2 * kPlaneBytes + nl * 8);
+        }
+    };
 
     uintx4 stage[XL];
-    uintx4 p1[4], p2[4], np1[4], np2[4];
-    uintx2 sc[4], nsc[4];
+    TileRecs ra, rb;
 #pragma unroll
     for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j]);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        p1[r] = load_global<uintx4>(rec[r] + lane * 16);
-        p2[r] = load_global<uintx4>(rec[r] + kPlaneBytes + lane * 16);
-        sc[r] = load_global<uintx2>(rec[r] + 2 * kPlaneBytes + nl * 8);
-        np1[r] = p1[r]; np2[r] = p2[r]; nsc[r] = sc[r];
-    }
+    load_recs(ra, 0);
+    rb = ra;
 #pragma unroll
     for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(xdst + j * 16 * kTileXStride) = stage[j];
     __syncthreads();
 
-    for (int ks = 0; ks < KS; ++ks) {
+    // one 256-column step: two scale groups from `cur`, while `nxt` is filled for step ks+1
+    auto step = [&](const TileRecs &cur, TileRecs &nxt, int ks) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int g = ks * 2 + h;
@@ -750,43 +761,38 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
 #pragma unroll
                     for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j] + (g + 1) * 128);
                 }
-                if (h == 1 && ks + 1 < KS) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const uint8_t *nr = rec[r] + static_cast<size_t>(ks + 1) * kRecordBytes;
-                        np1[r] = load_global<uintx4>(nr + lane * 16);
-                        np2[r] = load_global<uintx4>(nr + kPlaneBytes + lane * 16);
-                        nsc[r] = load_global<uintx2>(nr + 2 * kPlaneBytes + nl * 8);
-                    }
-                }
+                if (h == 0 && ks + 1 < KS) load_recs(nxt, ks + 1);
                 const char *xb = xop + (g & 1) * (TM * kTileXStride);
                 half8 al1[4], al2[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].x >> 16) : (sc[r].x & 0xffffu)));
-                    const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].y >> 16) : (sc[r].y & 0xffffu)));
+                    const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (cur.sc[r].x >> 16) : (cur.sc[r].x & 0xffffu)));
+                    const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (cur.sc[r].y >> 16) : (cur.sc[r].y & 0xffffu)));
                     al1[r] = half8{a1, a1, a1, a1, a1, a1, a1, a1};
                     al2[r] = half8{a2, a2, a2, a2, a2, a2, a2, a2};
                 }
 #pragma unroll
                 for (int fm = 0; fm < 4; ++fm) {
                     const int wi = 2 * h + (fm >> 1), par = fm & 1;
-                    half8 b1[4], b2[4];
+                    half8 b[2][4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        b1[r] = decode8(p1[r][wi], par) * al1[r];
-                        b2[r] = decode8(p2[r][wi], par) * al2[r];
+                        b[0][r] = decode8(cur.p1[r][wi], par) * al1[r];
+                        b[1][r] = decode8(cur.p2[r][wi], par) * al2[r];
                     }
+                    half8 a[MTW];
 #pragma unroll
-                    for (int mt = 0; mt < 4; ++mt) {
-                        const half8 a = __builtin_bit_cast(
+                    for (int mt = 0; mt < MTW; ++mt)
+                        a[mt] = __builtin_bit_cast(
                             half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * kTileXStride + fm * 64));
+                    // consecutive MFMAs write different accumulators
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b1[r], acc[r][mt], 0, 0, 0);
-                            acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b2[r], acc[r][mt], 0, 0, 0);
-                        }
-                    }
+                    for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+                        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b[pl][r], acc[r][mt], 0, 0, 0);
                 }
                 if (more) {
                     char *d = xdst + ((g + 1) & 1) * (TM * kTileXStride);
@@ -796,8 +802,11 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
                 __syncthreads();
             }
         }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) { p1[r] = np1[r]; p2[r] = np2[r]; sc[r] = nsc[r]; }
+    };
+
+    for (int ks = 0; ks < KS; ks += 2) {
+        step(ra, rb, ks);
+        if (ks + 1 < KS) step(rb, ra, ks + 1);
     }
 
 #pragma unroll
@@ -806,10 +815,10 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
         const int n = rt * kTileRows + nl;
         if (rt < RT && n < N) {
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int m = m0 + wm * 64 + mt * 16 + 4 * q + j;
+                    const int m = m0 + mt * 16 + 4 * q + j;
                     if (m < M) {
                         const size_t off = static_cast<size_t>(m) * N + n;
                         if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(acc[r][mt][j]);
@@ -820,36 +829,38 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     }
 }
 
-template <int WGM>
+template <int MTW>
 hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
                             hipStream_t stream)
 {
-    constexpr int TM = 64 * WGM, NRT = 4 * (4 / WGM);
+    constexpr int TM = 16 * MTW, NRT = 16;
     const int MB = (M + TM - 1) / TM;
     const int NB = static_cast<int>((s.RT + NRT - 1) / NRT);
     const int64_t grid = static_cast<int64_t>((NB + 7) / 8) * 8 * MB;
     const size_t lds = 2 * static_cast<size_t>(TM) * kTileXStride;
     static bool configured = false;                  // raise the dynamic LDS limit once per process
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<WGM>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<MTW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((gemm_tile_kernel<WGM>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
+    hipLaunchKernelGGL((gemm_tile_kernel<MTW>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
                        static_cast<int>(s.KS), y_f16, MB, NB);
     return hipGetLastError();
 }
 
-int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1;
+int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0;
 
 template <int MT, int R, int S>
 hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
                              hipStream_t stream)
 {
-    int W = g_tune_small_waves > 0 ? g_tune_small_waves : 4;
-    if (W > 8) W = 8;
+    // measured on 8B shapes: 8 waves per item, except for the register-heavy 64-token x 2-tile case
+    int W = g_tune_small_waves > 0 ? g_tune_small_waves : (MT * R >= 8 ? 2 : 8);
+    if (W > (MT * R >= 8 ? 4 : 8)) W = MT * R >= 8 ? 4 : 8;
+    while (W > 1 && W > s.KS) W /= 2;
     const int grid = static_cast<int>((s.RT + R - 1) / R);
     size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
     if (lds < static_cast<size_t>(W) * kBounceBytes) lds = static_cast<size_t>(W) * kBounceBytes;
@@ -881,6 +892,20 @@ int pick_waves(int64_t KS, int wmax) {
     return W < 1 ? 1 : W;
 }
 
+// 2..64 tokens: the small-batch item kernel in the shape that measured best
+hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int f16,
+                        hipStream_t stream)
+{
+    // many row tiles: two per item share one set of activation operands
+    const int R = g_tune_small_rows > 0 ? g_tune_small_rows : (s.RT >= 512 ? 2 : 1);
+    if (M <= 16) return R == 2 ? launch_gemm_items<1, 2, 1>(records, x, y, M, s, f16, stream)
+                               : launch_gemm_items<1, 1, 2>(records, x, y, M, s, f16, stream);
+    if (M <= 32) return R == 2 ? launch_gemm_items<2, 2, 1>(records, x, y, M, s, f16, stream)
+                               : launch_gemm_items<2, 1, 1>(records, x, y, M, s, f16, stream);
+    return R == 2 ? launch_gemm_items<4, 2, 1>(records, x, y, M, s, f16, stream)
+                  : launch_gemm_items<4, 1, 1>(records, x, y, M, s, f16, stream);
+}
+
 ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M,
                          int64_t N, int64_t K, int32_t group, void *stream_, int64_t max_m)
 {
@@ -908,13 +933,22 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
         if (R >= 4) e = launch_gemv<1, 4, true>(records, x, y, Mi, s, W, f16, stream);
         else if (R >= 2) e = launch_gemv<1, 2, true>(records, x, y, Mi, s, W, f16, stream);
         else e = launch_gemv<1, 1, true>(records, x, y, Mi, s, W, f16, stream);
-    } else if (M > PTQTP_GEMM_SMALL_MAX_M || g_tune_tile == 1) {
-        if (M <= 64) e = launch_gemm_tile<1>(records, x, y, Mi, s, f16, stream);
-        else e = launch_gemm_tile<2>(records, x, y, Mi, s, f16, stream);
+    } else if (M >= 256 || g_tune_tile == 1) {
+        if (M <= 64) e = launch_gemm_tile<4>(records, x, y, Mi, s, f16, stream);
+        else e = launch_gemm_tile<8>(records, x, y, Mi, s, f16, stream);
+    } else if (M > PTQTP_GEMM_SMALL_MAX_M) {
+        // 65..255 tokens: too few token blocks to fill the chip with 256-row tiles; run the
+        // small-batch kernel on chunks of 64 tokens instead
+        e = hipSuccess;
+        for (int m0 = 0; m0 < Mi && e == hipSuccess; m0 += 64) {
+            const int mc = Mi - m0 < 64 ? Mi - m0 : 64;
+            const uint16_t *xc = x + static_cast<size_t>(m0) * s.K;
+            void *yc = static_cast<char *>(y) + static_cast<size_t>(m0) * s.N * (f16 ? 2 : 4);
+            e = launch_small(records, xc, yc, mc, s, f16, stream);
+        }
     } else if (g_tune_small != 0) {
-        if (M <= 16) e = launch_gemm_items<1, 1, 2>(records, x, y, Mi, s, f16, stream);
-        else if (M <= 32) e = launch_gemm_items<2, 1, 1>(records, x, y, Mi, s, f16, stream);
-        else e = launch_gemm_items<4, 1, 1>(records, x, y, Mi, s, f16, stream);
+        // many row tiles: two per item share one set of activation operands
+        e = launch_small(records, x, y, Mi, s, f16, stream);
     } else if (M <= 16) {
         const int W = pick_waves(s.KS, 16);
         int R = g_tune_rows > 0 ? g_tune_rows : (s.RT >= 4096 ? 2 : 1);
@@ -1110,6 +1144,11 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!strcmp(key, "tile")) {
         if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
         g_tune_tile = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "small_rows")) {
+        if (value < 0 || value > 2) return PTQTP_ERR_SHAPE;
+        g_tune_small_rows = value;
         return PTQTP_OK;
     }
     if (!strcmp(key, "small_waves")) {

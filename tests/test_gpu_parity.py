@@ -289,6 +289,20 @@ def test_gemm_small_shapes(ptq, N, K, M):
     check(ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K), lin, x)
 
 
+@pytest.mark.parametrize("rows,waves", [(1, 1), (1, 8), (2, 2), (2, 4), (2, 8)])
+def test_gemm_small_launch_shapes(ptq, rows, waves):
+    try:
+        ptq.ptqtp_tune("small_rows", rows)
+        ptq.ptqtp_tune("small_waves", waves)
+        for N, K, M in [(200, 2304, 9), (1000, 640, 33), (48, 4096, 64), (8200, 256, 5)]:
+            lin = workloads.make_linear(N, K, 65, N)
+            x = workloads.make_x(M, K, 65, N)
+            check(ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K), lin, x)
+    finally:
+        ptq.ptqtp_tune("small_rows", 0)
+        ptq.ptqtp_tune("small_waves", 0)
+
+
 # ---------------------------------------------------------------- MFMA tile (large batch / prefill)
 @pytest.mark.parametrize("N,K,M", [(528, 2048, 65), (528, 2048, 128), (200, 1024, 130), (1000, 640, 257),
                                     (64, 128, 300), (2048, 4096, 512), (16, 384, 70), (4096, 256, 96)])
