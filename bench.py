@@ -119,7 +119,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run 5 plain 1 GiB device copies (known HBM traffic) and exit: the reference that "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
-    ap.add_argument("--per-shape", action="store_true", help="also time every shape on its own (hot and cold)")
+    ap.add_argument("--per-shape", action="store_true",
+                    help="also time the other configs one linear per launch: 8B shapes at M = 1/4/16/64, 70B shapes at "
+                         "M = 1/32 and prefill M = 2048")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path needs no second device); use --gpus 1",
@@ -206,34 +208,59 @@ def recorded_traffic(mode: str, layers: int):
     return None
 
 
-def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, reps=200):
-    """Each distinct shape on its own: `cold` walks the 32 layer copies, `hot` re-runs layer 0's blob."""
-    res = {}
+def _graph_time(torch, stream, run, launches, reps=10):
+    """us per launch of `run` (which enqueues `launches` library calls), replayed from a hipGraph."""
+    run()
+    stream.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        run()
+    g.replay()
+    stream.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        g.replay()
+    e1.record(stream)
+    stream.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (reps * launches)
+
+
+def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream):
+    """The other BASELINE configs, one linear per launch (not the headline):
+    config 1/2: each 8B shape at M = 1, 4, 16, 64, cold (walking the 32 layer copies) -- and M = 1 hot;
+    config 4:   70B shapes at M = 1 and 32 (hot: one copy) and prefill M = 2048 on the MFMA tile."""
+    import workloads
+    res = {"8b": {}, "70b": {}}
+    dev = xs[0].device
     with torch.cuda.stream(stream):
         for name in ("q", "k", "gate", "down"):
             idxs = [i for i, j in enumerate(jobs) if j[1] == name]
             n, k = dims[idxs[0]]
-            for label, seq in (("cold", idxs), ("hot", idxs[:1])):
-                g = torch.cuda.CUDAGraph()
-                order = [seq[i % len(seq)] for i in range(reps)]
-                for i in order[:4]:
-                    ptq.ptqtp_gemv(blobs[i], xs[i], n, k, out=ys[i])
-                stream.synchronize()
-                with torch.cuda.graph(g, stream=stream):
-                    for i in order:
-                        ptq.ptqtp_gemv(blobs[i], xs[i], n, k, out=ys[i])
-                g.replay()
-                stream.synchronize()
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                for _ in range(5):
-                    g.replay()
-                e1.record(stream)
-                stream.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / (5 * reps)
-                res[f"{name}_{n}x{k}_{label}"] = {"us": round(us, 3),
-                                                  "GBps": round(algorithmic_bytes(n, k) / us / 1e3, 1)}
+            for M in (1, 4, 16, 64):
+                x = torch.randn(M, k, device=dev).half()
+                y = torch.empty(M, n, device=dev)
+                us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blobs[i], x, n, k, out=y) for i in idxs], len(idxs))
+                res["8b"][f"{name}_{n}x{k}_M{M}_cold"] = {"us": round(us, 2), "GBps": round(algorithmic_bytes(n, k, M) / us / 1e3, 1)}
+            x = xs[idxs[0]].reshape(1, -1)
+            y = ys[idxs[0]]
+            us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blobs[idxs[0]], x, n, k, out=y) for _ in range(32)], 32)
+            res["8b"][f"{name}_{n}x{k}_M1_hot"] = {"us": round(us, 2), "GBps": round(algorithmic_bytes(n, k, 1) / us / 1e3, 1)}
+        for name in ("q", "k", "gate", "down"):
+            lin = workloads.linear_70b(name)
+            n, k = lin["N"], lin["K"]
+            blob = ptq.ptqtp_pack(*(torch.from_numpy(lin[key]).to(dev) for key in ("T1", "T2", "a1", "a2")), check=False)
+            del lin
+            for M in (1, 32, 2048):
+                x = torch.randn(M, k, device=dev).half()
+                y = torch.empty(M, n, device=dev)
+                us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blob, x, n, k, out=y) for _ in range(4)], 4, reps=5)
+                ent = {"us": round(us, 2), "GBps": round(algorithmic_bytes(n, k, M) / us / 1e3, 1)}
+                if M == 2048:
+                    ent["TFLOPs"] = round(4.0 * M * n * k / us / 1e6, 1)      # two planes: 2*2*M*N*K
+                res["70b"][f"{name}_{n}x{k}_M{M}"] = ent
+            del blob
     return res
 
 
