@@ -20,6 +20,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ptqtp_oracle.c")
+_SRC_Q = os.path.join(_HERE, "ptqtp_quantizer_oracle.c")
 _LIB = os.path.join(_HERE, "libptqtp_oracle.so")
 _lib = None
 
@@ -34,10 +35,11 @@ class OracleError(ValueError):
 
 def build(force: bool = False) -> str:
     """Compile ptqtp_oracle.c with gcc (-O2, OpenMP for the row loop)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_Q))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-                               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+                               "-ffp-contract=off", "-o", tmp, _SRC, _SRC_Q, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -59,6 +61,10 @@ def _load():
         lib.ptqtp_oracle_unpack_canonical.argtypes = [p, i64, i64, p]
         lib.ptqtp_oracle_model_bits.restype = i64
         lib.ptqtp_oracle_model_bits.argtypes = [i64, i64, i64]
+        lib.ptqtp_oracle_quantize.restype = i32
+        lib.ptqtp_oracle_quantize.argtypes = [p, i64, i64, i64, i32, ctypes.c_double, p, p, p, p, p, p, p, p]
+        lib.ptqtp_oracle_double_to_half_bits.restype = ctypes.c_uint16
+        lib.ptqtp_oracle_double_to_half_bits.argtypes = [ctypes.c_double]
         _lib = lib
     return _lib
 
@@ -154,3 +160,33 @@ def unpack_canonical(packed, K: int) -> np.ndarray:
 
 def model_bits(n: int, d: int, group: int = 128) -> int:
     return int(_load().ptqtp_oracle_model_bits(n, d, group))
+
+
+def double_to_half_bits(f: float) -> int:
+    return int(_load().ptqtp_oracle_double_to_half_bits(float(f)))
+
+
+def quantize(W, group: int = 128, max_iters: int = 50, eps: float = 1e-4) -> dict:
+    """PTQTP decomposition of W (float16 [N,K]) -> dict(T1, T2 int8 [N,K]; a1, a2 float16 [N,K/group];
+    a1_f64, a2_f64 float64 (the iteration's alpha); lam float64; iters int).  See ptqtp_quantizer_oracle.c."""
+    W = np.ascontiguousarray(W)
+    if W.dtype != np.float16 or W.ndim != 2:
+        raise TypeError("W must be a float16 matrix")
+    N, K = W.shape
+    if K % group:
+        raise OracleError(ERR_SHAPE)
+    ng = K // group
+    out = {"T1": np.empty((N, K), np.int8), "T2": np.empty((N, K), np.int8),
+           "a1_f64": np.empty((N, ng), np.float64), "a2_f64": np.empty((N, ng), np.float64),
+           "a1": np.empty((N, ng), np.float16), "a2": np.empty((N, ng), np.float16),
+           "lam": np.empty((N, ng), np.float64)}
+    iters = ctypes.c_int(0)
+    ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    rc = _load().ptqtp_oracle_quantize(ptr(W.view(np.uint16)), N, K, group, int(max_iters), float(eps),
+                                       ptr(out["T1"]), ptr(out["T2"]), ptr(out["a1_f64"]), ptr(out["a2_f64"]),
+                                       ptr(out["a1"].view(np.uint16)), ptr(out["a2"].view(np.uint16)),
+                                       ptr(out["lam"]), ctypes.byref(iters))
+    if rc != OK:
+        raise OracleError(rc)
+    out["iters"] = iters.value
+    return out

@@ -668,7 +668,10 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
 // fp32 accumulator -- then issues 8*MTW MFMAs per 32-column field against MTW LDS operand reads.
 // Workgroups are numbered so that all token blocks of a row block run on the same XCD and
 // share its L2 copy of the packed rows.
-constexpr int kTileXStride = 272;                    // bytes per token row of the LDS x tile (128 fp16 + pad)
+#ifndef PTQTP_TILE_STRIDE
+#define PTQTP_TILE_STRIDE 272
+#endif
+constexpr int kTileXStride = PTQTP_TILE_STRIDE;     // bytes per token row of the LDS x tile (128 fp16 + pad)
 
 __device__ __forceinline__ half8 decode8(uint32_t word, int parity) {
     const uint32_t fp4 = (parity ? (word << 1) : word) & 0xAAAAAAAAu;
