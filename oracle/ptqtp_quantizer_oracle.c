@@ -71,7 +71,7 @@ static uint16_t double_to_half_bits(double f)
     int e;
     (void)frexp(a, &e);                                                           /* a = m * 2^e, m in [0.5, 1) */
     e -= 1;                                                                       /* a in [2^e, 2^(e+1)) */
-    if (e < -14) e = -14;
+    if (e < -14 || a == 0.0) e = -14;                                             /* subnormal range, zero */
     const double q = ldexp(a, 10 - e);                                            /* exact: in units of the spacing */
     double r = floor(q);
     const double rem = q - r;                                                     /* exact */
