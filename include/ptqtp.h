@@ -170,6 +170,31 @@ ptqtp_status ptqtp_gemv_batch_plan(const ptqtp_linear *linears, int32_t count, i
 ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream);
 
 /*
+ * The step before the path: PTQTP decomposition of an fp16 weight matrix into the two trit
+ * planes and scales that ptqtp_pack takes (paper, Sec. "Dual Trit-planes Approximation" and
+ * "Progressive Optimization", both algorithm listings): per (row, group) unit, initialise
+ * T1 = T2 = sign(w) (0 -> +1), alpha = [1,1], lambda = 1e-8; then up to max_iters times solve the
+ * 2x2 ridge system alpha = (S'S + lambda I)^-1 S'w (lambda raised to min(1, lambda*sqrt(kappa/1e6))
+ * first when kappa = ||A||_F ||A^-1||_F >= 1e6) and re-pick every trit pair as the first minimiser of
+ * (w - alpha1 c1 - alpha2 c2)^2 over the nine pairs in the order c1 = -1,0,1 (outer), c2 = -1,0,1
+ * (inner); stop when the Frobenius norm of the change of all scales of the matrix is below eps.
+ * The paper's settings are max_iters = 50, eps = 1e-4.  All arithmetic that decides a trit is
+ * binary64 and reproducible; the scales are stored as their binary16 rounding.
+ *
+ *   W           device, fp16 bits [N, K] row-major (finite values)
+ *   T1, T2      device, int8 [N, K], overwritten (also used as state between iterations)
+ *   a1, a2      device, fp16 bits [N, K/group], overwritten
+ *   iters       device int32 or NULL: receives the number of iterations performed
+ *   workspace   device, >= ptqtp_quantize_workspace_bytes(N, K, group) bytes, 256-byte aligned
+ * Stream-ordered, never synchronises: 2 launches per iteration; once the stopping rule has fired
+ * the remaining launches return immediately.
+ */
+size_t ptqtp_quantize_workspace_bytes(int64_t N, int64_t K, int32_t group);
+ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t group, int32_t max_iters, double eps,
+                            int8_t *T1, int8_t *T2, uint16_t *a1, uint16_t *a2, int32_t *iters,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Tuning hook for benchmarks and sweeps (not needed for correct use): override
  * the launch shape the compute calls pick.  key = "gemv_waves" (waves per
  * workgroup, 1..16), "gemv_rows" (16-row tiles per workgroup, 1, 2 or 4),

@@ -63,6 +63,10 @@ def _load():
         lib.ptqtp_gemv_batch_plan.argtypes = [p, i32, i32, i32, p, sz, p]
         lib.ptqtp_gemv_batch.restype = i32
         lib.ptqtp_gemv_batch.argtypes = [p, i64, p]
+        lib.ptqtp_quantize_workspace_bytes.restype = sz
+        lib.ptqtp_quantize_workspace_bytes.argtypes = [i64, i64, i32]
+        lib.ptqtp_quantize.restype = i32
+        lib.ptqtp_quantize.argtypes = [p, i64, i64, i32, i32, ctypes.c_double, p, p, p, p, p, p, sz, p]
         lib.ptqtp_tune.restype = i32
         lib.ptqtp_tune.argtypes = [ctypes.c_char_p, i32]
         _lib = lib
@@ -206,3 +210,24 @@ def ptqtp_gemv_batch(plan: BatchPlan) -> None:
     st = _load().ptqtp_gemv_batch(plan.plan.data_ptr(), plan.items, _stream())
     if st:
         raise PtqtpError(st, "ptqtp_gemv_batch")
+
+
+def ptqtp_quantize(W: torch.Tensor, group: int = 128, max_iters: int = 50, eps: float = 1e-4):
+    """PTQTP decomposition of W (fp16 [N,K] on the GPU) -> (T1, T2 int8 [N,K], a1, a2 fp16 [N,K/group], iters int32[1])."""
+    N, K = W.shape
+    lib = _load()
+    nbytes = int(lib.ptqtp_quantize_workspace_bytes(N, K, group))
+    if nbytes == 0:
+        raise PtqtpError(2 if group == 128 else 3, "ptqtp_quantize_workspace_bytes")
+    dev = W.device
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    T1 = torch.empty((N, K), dtype=torch.int8, device=dev)
+    T2 = torch.empty((N, K), dtype=torch.int8, device=dev)
+    a1 = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+    a2 = torch.empty((N, K // group), dtype=torch.float16, device=dev)
+    iters = torch.zeros(1, dtype=torch.int32, device=dev)
+    st = lib.ptqtp_quantize(_dev(W, torch.float16, "W"), N, K, group, int(max_iters), float(eps), T1.data_ptr(),
+                            T2.data_ptr(), a1.data_ptr(), a2.data_ptr(), iters.data_ptr(), ws.data_ptr(), nbytes, _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_quantize")
+    return T1, T2, a1, a2, iters

@@ -6,7 +6,7 @@ import subprocess
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SOURCES = [os.path.join(PKG, "csrc", "ptqtp.hip")]
+SOURCES = [os.path.join(PKG, "csrc", "ptqtp.hip"), os.path.join(PKG, "csrc", "ptqtp_quantize.hip")]
 LIB = os.path.join(PKG, "libptqtp.so")
 
 HIPCC_FLAGS = [

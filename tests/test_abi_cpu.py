@@ -28,7 +28,9 @@ def lib():
 def test_header_symbols_exported(lib):
     names = _declared()
     assert {"ptqtp_pack", "ptqtp_unpack", "ptqtp_gemv", "ptqtp_gemm_small", "ptqtp_packed_bytes",
-            "ptqtp_workspace_bytes", "ptqtp_status_string", "ptqtp_version", "ptqtp_tune"} <= set(names)
+            "ptqtp_workspace_bytes", "ptqtp_status_string", "ptqtp_version", "ptqtp_tune", "ptqtp_gemm",
+            "ptqtp_gemv_batch", "ptqtp_gemv_batch_plan", "ptqtp_batch_items", "ptqtp_batch_plan_bytes",
+            "ptqtp_quantize", "ptqtp_quantize_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in ptqtp.h but not exported"
 
@@ -75,6 +77,26 @@ def test_batch_plan_validation(lib):
     assert lib.ptqtp_gemv_batch_plan(arr, 3, 0, 128, fake, 1 << 20, None) == 6
     assert lib.ptqtp_gemv_batch(None, 5, None) == 1
     assert lib.ptqtp_gemv_batch(fake, 0, None) == 2
+
+
+def test_quantize_validation(lib):
+    fake = ctypes.c_void_p(0x10000)
+    assert lib.ptqtp_quantize_workspace_bytes(4096, 4096, 128) == 256 + 4096 * 32 * 32
+    assert lib.ptqtp_quantize_workspace_bytes(4096, 4000, 128) == 0
+    assert lib.ptqtp_quantize_workspace_bytes(4096, 4096, 64) == 0
+    big = 1 << 30
+    args = lambda **k: [k.get("W", fake), k.get("N", 64), k.get("K", 256), k.get("group", 128), k.get("iters", 50),
+                        ctypes.c_double(k.get("eps", 1e-4)), fake, fake, fake, fake, None, k.get("ws", fake),
+                        k.get("wsb", big), None]
+    assert lib.ptqtp_quantize(*args(W=None)) == 1
+    assert lib.ptqtp_quantize(*args(ws=None)) == 1
+    assert lib.ptqtp_quantize(*args(group=64)) == 3
+    assert lib.ptqtp_quantize(*args(K=200)) == 2
+    assert lib.ptqtp_quantize(*args(iters=-1)) == 2
+    assert lib.ptqtp_quantize(*args(eps=-1.0)) == 2
+    assert lib.ptqtp_quantize(*args(eps=float("nan"))) == 2
+    assert lib.ptqtp_quantize(*args(wsb=100)) == 4
+    assert lib.ptqtp_quantize(*args(ws=ctypes.c_void_p(0x10010))) == 6
 
 
 def test_status_strings_and_version(lib):
