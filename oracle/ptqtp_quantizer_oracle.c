@@ -106,13 +106,14 @@ static double unit_iteration(const uint16_t *w16, int G, int8_t *t1, int8_t *t2,
     double p = A11 * A22;
     const double qq = A12 * A12;
     double det = p - qq;
-    /* kappa = ||A||_F * ||A^-1||_F with A^-1 = adj(A) / det */
+    /* A^-1 = (1 / det) * [[A22, -A12], [-A12, A11]]  (closed form of the appendix), kappa = ||A||_F * ||A^-1||_F */
     double sq = A11 * A11;
     sq = sq + A12 * A12;
     sq = sq + A12 * A12;
     sq = sq + A22 * A22;
     const double nA = sqrt(sq);
-    const double i11 = A22 / det, i12 = -A12 / det, i22 = A11 / det;
+    double rdet = 1.0 / det;
+    double i11 = A22 * rdet, i12 = -A12 * rdet, i22 = A11 * rdet;
     double si = i11 * i11;
     si = si + i12 * i12;
     si = si + i12 * i12;
@@ -128,11 +129,16 @@ static double unit_iteration(const uint16_t *w16, int G, int8_t *t1, int8_t *t2,
         A22 = (double)s22 + lam;
         p = A11 * A22;
         det = p - qq;
+        rdet = 1.0 / det;
+        i11 = A22 * rdet;
+        i12 = -A12 * rdet;
+        i22 = A11 * rdet;
     }
     *lambda = lam;
-    const double n1 = A22 * b1, n1b = A12 * b2;
-    const double n2 = A11 * b2, n2b = A12 * b1;
-    const double a1 = (n1 - n1b) / det, a2 = (n2 - n2b) / det;
+    /* alpha = A^-1 b */
+    const double m11 = i11 * b1, m12 = i12 * b2;
+    const double m21 = i12 * b1, m22 = i22 * b2;
+    const double a1 = m11 + m12, a2 = m21 + m22;
     for (int j = 0; j < G; ++j) {
         const double w = half_bits_to_double(w16[j]);
         double best = INFINITY;

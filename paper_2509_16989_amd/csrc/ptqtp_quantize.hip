@@ -8,10 +8,11 @@
 // the appendix closed-form 2x2 inverse.  One (row, 128-column group) unit is decomposed on its own
 // ("Batch Processing").
 //
-// Mapping: one wave per unit, two elements per lane, state (trits) in HBM between iterations:
+// Mapping: 16 units per wave (four lanes x 32 elements per unit), state (trits) in HBM between iterations:
 // 6 bytes per weight per iteration (2 read for w, 2 read + 2 written for the trit pair), so an
 // iteration is HBM-bound like the forward path.  The sums S'S (small integers) and S'w (w * 2^24
-// is an integer: exact in 64-bit) are wave reductions over integers; the 2x2 solve and the search
+// is an integer: exact in 64-bit) are integer sums (32 per lane, then across the four lanes of the
+// unit); the 2x2 solve and the search
 // run in binary64, one operation at a time with contraction off, so the integer decisions are
 // reproducible bit for bit.  The stopping rule needs a matrix-wide sum: every iteration is two
 // launches (units, then a fixed-order reduction that sets a device flag); later launches see the
@@ -69,14 +70,17 @@ __device__ __forceinline__ uint16_t double_to_half_rne(double f) {
     return static_cast<uint16_t>(sign | static_cast<uint32_t>(hm));
 }
 
-__device__ __forceinline__ int wave_sum_i32(int v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+// sums over the four lanes that share a unit (lanes 4i .. 4i+3)
+__device__ __forceinline__ int quad_sum_i32(int v) {
+    v += __shfl_xor(v, 1, 64);
+    v += __shfl_xor(v, 2, 64);
     return v;
 }
-__device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
+__device__ __forceinline__ int64_t quad_sum_i64(int64_t v) {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
+    for (int o = 1; o <= 2; o <<= 1) {
         const int lo = __shfl_xor(static_cast<int>(v & 0xffffffff), o, 64);
         const int hi = __shfl_xor(static_cast<int>(v >> 32), o, 64);
         v += (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
@@ -84,7 +88,9 @@ __device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
     return v;
 }
 
-// One iteration for every unit.  FIRST: the state is the initialisation (no trits in memory yet).
+// One iteration for every unit.  A wave holds 16 units: lane l works on elements (l%4)*32 .. +31 of
+// unit l/4, so the 2x2 solve (the same for all lanes of a unit) is repeated 4 times, not 64.
+// FIRST: the state is the initialisation (no trits in memory yet).
 template <bool FIRST>
 __global__ void __launch_bounds__(256)
 quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_t *__restrict__ T2,
@@ -93,35 +99,57 @@ quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_
 {
 #pragma clang fp contract(off)
     if (flags->done) return;
-    const int lane = threadIdx.x & 63;
-    const int64_t u = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (u >= units) return;
+    const int lane = threadIdx.x & 63, part = lane & 3;
+    const int64_t u_raw = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (lane >> 2);
+    const bool valid = u_raw < units;
+    const int64_t u = valid ? u_raw : units - 1;       // idle lanes shadow the last unit and store nothing
     const int64_t n = u / NG, g = u % NG;
-    const int64_t off = n * K + g * kGroup + 2 * lane;
-    const uint32_t wp = *reinterpret_cast<const uint32_t *>(W + off);
-    const uint32_t h0 = wp & 0xffffu, h1 = wp >> 16;
-    int t10, t11, t20, t21;
+    const int64_t off = n * K + g * kGroup + part * 32;
+
+    uint32_t wv[16];                                   // 32 fp16 weights
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uintx4 v = *reinterpret_cast<const uintx4 *>(W + off + 8 * i);
+        wv[4 * i] = v.x; wv[4 * i + 1] = v.y; wv[4 * i + 2] = v.z; wv[4 * i + 3] = v.w;
+    }
+    uint32_t tv1[8], tv2[8];                           // 32 trits per plane, one byte each
     double lam, ap1, ap2;
     if (FIRST) {
-        // sign(w) with 0 -> +1; -0.0 counts as zero
-        t10 = t20 = ((h0 & 0x8000u) && (h0 & 0x7fffu)) ? -1 : 1;
-        t11 = t21 = ((h1 & 0x8000u) && (h1 & 0x7fffu)) ? -1 : 1;
         lam = 1.0e-8; ap1 = 1.0; ap2 = 1.0;
     } else {
-        const uint16_t p1 = *reinterpret_cast<const uint16_t *>(T1 + off);
-        const uint16_t p2 = *reinterpret_cast<const uint16_t *>(T2 + off);
-        t10 = static_cast<int8_t>(p1 & 0xff); t11 = static_cast<int8_t>(p1 >> 8);
-        t20 = static_cast<int8_t>(p2 & 0xff); t21 = static_cast<int8_t>(p2 >> 8);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uintx4 a = *reinterpret_cast<const uintx4 *>(T1 + off + 16 * i);
+            const uintx4 b = *reinterpret_cast<const uintx4 *>(T2 + off + 16 * i);
+            tv1[4 * i] = a.x; tv1[4 * i + 1] = a.y; tv1[4 * i + 2] = a.z; tv1[4 * i + 3] = a.w;
+            tv2[4 * i] = b.x; tv2[4 * i + 1] = b.y; tv2[4 * i + 2] = b.z; tv2[4 * i + 3] = b.w;
+        }
         lam = lambda[u]; ap1 = alpha[2 * u]; ap2 = alpha[2 * u + 1];
     }
-    const int64_t f0 = half_to_fixed24(h0), f1 = half_to_fixed24(h1);
-    // S'S: three small integers in one word (each sum is at most 128 in magnitude; s12 is signed)
-    const int packed = (t10 * t10 + t11 * t11) | ((t20 * t20 + t21 * t21) << 10) | ((t10 * t20 + t11 * t21 + 2) << 20);
-    const int ps = wave_sum_i32(packed);
-    const int s11 = ps & 0x3ff, s22 = (ps >> 10) & 0x3ff, s12 = ((ps >> 20) & 0x3ff) - 2 * 64;
-    const int64_t B1 = wave_sum_i64(t10 * f0 + t11 * f1), B2 = wave_sum_i64(t20 * f0 + t21 * f1);
+
+    int s11 = 0, s22 = 0, s12 = 0;
+    int64_t B1 = 0, B2 = 0;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const uint32_t h = (wv[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+        int t1, t2;
+        if (FIRST) {
+            t1 = t2 = ((h & 0x8000u) && (h & 0x7fffu)) ? -1 : 1;     // sign(w) with 0 -> +1; -0.0 counts as zero
+        } else {
+            t1 = static_cast<int8_t>((tv1[e >> 2] >> (8 * (e & 3))) & 0xffu);
+            t2 = static_cast<int8_t>((tv2[e >> 2] >> (8 * (e & 3))) & 0xffu);
+        }
+        const int64_t f = half_to_fixed24(h);
+        s11 += t1 * t1; s22 += t2 * t2; s12 += t1 * t2;
+        B1 += t1 * f; B2 += t2 * f;
+    }
+    // S'S: three small integers in one word (unit sums are at most 128 in magnitude; s12 is signed)
+    const int ps = quad_sum_i32(s11 | (s22 << 10) | ((s12 + 32) << 20));
+    s11 = ps & 0x3ff; s22 = (ps >> 10) & 0x3ff; s12 = ((ps >> 20) & 0x3ff) - 128;
+    B1 = quad_sum_i64(B1); B2 = quad_sum_i64(B2);
     const double b1 = static_cast<double>(B1) * 0x1p-24, b2 = static_cast<double>(B2) * 0x1p-24;   // exact
 
+    // ridge normal equations, closed-form inverse A^-1 = (1/det) adj(A), kappa = ||A||_F ||A^-1||_F
     const double A12 = static_cast<double>(s12);
     double A11 = static_cast<double>(s11) + lam, A22 = static_cast<double>(s22) + lam;
     double p = A11 * A22;
@@ -132,7 +160,8 @@ quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_
     sq = sq + A12 * A12;
     sq = sq + A22 * A22;
     const double nA = __dsqrt_rn(sq);
-    const double i11 = __ddiv_rn(A22, det), i12 = __ddiv_rn(-A12, det), i22 = __ddiv_rn(A11, det);
+    double rdet = __ddiv_rn(1.0, det);
+    double i11 = A22 * rdet, i12 = -A12 * rdet, i22 = A11 * rdet;
     double si = i11 * i11;
     si = si + i12 * i12;
     si = si + i12 * i12;
@@ -148,10 +177,14 @@ quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_
         A22 = static_cast<double>(s22) + lam;
         p = A11 * A22;
         det = p - qq;
+        rdet = __ddiv_rn(1.0, det);
+        i11 = A22 * rdet;
+        i12 = -A12 * rdet;
+        i22 = A11 * rdet;
     }
-    const double n1 = A22 * b1, n1b = A12 * b2;
-    const double n2 = A11 * b2, n2b = A12 * b1;
-    const double a1 = __ddiv_rn(n1 - n1b, det), a2 = __ddiv_rn(n2 - n2b, det);
+    const double m11 = i11 * b1, m12 = i12 * b2;
+    const double m21 = i12 * b1, m22 = i22 * b2;
+    const double a1 = m11 + m12, a2 = m21 + m22;
 
     // nine candidate values in the order c1 = -1,0,1 (outer), c2 = -1,0,1 (inner)
     double cand[9];
@@ -159,31 +192,41 @@ quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_
     for (int c1 = -1; c1 <= 1; ++c1)
 #pragma unroll
         for (int c2 = -1; c2 <= 1; ++c2) cand[(c1 + 1) * 3 + (c2 + 1)] = static_cast<double>(c1) * a1 + static_cast<double>(c2) * a2;
-    uint32_t out1 = 0, out2 = 0;
+    uint32_t o1[8], o2[8];
 #pragma unroll
-    for (int el = 0; el < 2; ++el) {
-        const double w = half_to_double(el ? h1 : h0);
+    for (int i = 0; i < 8; ++i) { o1[i] = 0; o2[i] = 0; }
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const double w = half_to_double((wv[e >> 1] >> (16 * (e & 1))) & 0xffffu);
         double best = __builtin_inf();
         int bm = 0;
 #pragma unroll
         for (int m = 0; m < 9; ++m) {
             const double d = w - cand[m];
-            const double e = d * d;
-            if (e < best) { best = e; bm = m; }
+            const double err = d * d;
+            if (err < best) { best = err; bm = m; }
         }
-        const int c1 = bm / 3 - 1, c2 = bm % 3 - 1;
-        out1 |= (static_cast<uint32_t>(c1) & 0xffu) << (8 * el);
-        out2 |= (static_cast<uint32_t>(c2) & 0xffu) << (8 * el);
+        // bm -> (c1, c2) as bytes: c1 = bm/3 - 1, c2 = bm%3 - 1
+        const int c1 = (bm >= 6) - (bm < 3);
+        const int r3 = bm - 3 * (c1 + 1);
+        const int c2 = r3 - 1;
+        o1[e >> 2] |= (static_cast<uint32_t>(c1) & 0xffu) << (8 * (e & 3));
+        o2[e >> 2] |= (static_cast<uint32_t>(c2) & 0xffu) << (8 * (e & 3));
     }
-    *reinterpret_cast<uint16_t *>(T1 + off) = static_cast<uint16_t>(out1);
-    *reinterpret_cast<uint16_t *>(T2 + off) = static_cast<uint16_t>(out2);
-    if (lane == 0) {
-        const double d1 = a1 - ap1, d2 = a2 - ap2;
-        const double q1 = d1 * d1, q2 = d2 * d2;
-        alpha[2 * u] = a1;
-        alpha[2 * u + 1] = a2;
-        lambda[u] = lam;
-        delta2[u] = q1 + q2;
+    if (valid) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            *reinterpret_cast<uintx4 *>(T1 + off + 16 * i) = uintx4{o1[4 * i], o1[4 * i + 1], o1[4 * i + 2], o1[4 * i + 3]};
+            *reinterpret_cast<uintx4 *>(T2 + off + 16 * i) = uintx4{o2[4 * i], o2[4 * i + 1], o2[4 * i + 2], o2[4 * i + 3]};
+        }
+        if (part == 0) {
+            const double d1 = a1 - ap1, d2 = a2 - ap2;
+            const double q1 = d1 * d1, q2 = d2 * d2;
+            alpha[2 * u] = a1;
+            alpha[2 * u + 1] = a2;
+            lambda[u] = lam;
+            delta2[u] = q1 + q2;
+        }
     }
 }
 
@@ -261,7 +304,7 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
         return PTQTP_ERR_SHAPE;
     const size_t need = ptqtp_quantize_workspace_bytes(N, K, group);
     if (workspace_bytes < need) return PTQTP_ERR_SIZE;
-    if (!aligned(workspace, 256) || !aligned(W, 4) || !aligned(T1, 2) || !aligned(T2, 2) || !aligned(a1, 2) ||
+    if (!aligned(workspace, 256) || !aligned(W, 16) || !aligned(T1, 16) || !aligned(T2, 16) || !aligned(a1, 2) ||
         !aligned(a2, 2))
         return PTQTP_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
@@ -270,7 +313,7 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
     double *alpha = reinterpret_cast<double *>(flags + 1);
     double *lambda = alpha + 2 * units;
     double *delta2 = lambda + units;
-    const unsigned ublocks = static_cast<unsigned>((units + 3) / 4);
+    const unsigned ublocks = static_cast<unsigned>((units + 63) / 64);     // 4 waves x 16 units per workgroup
     hipLaunchKernelGGL(quant_begin_kernel, dim3(1), dim3(64), 0, stream, flags);
     if (max_iters == 0) {
         const int64_t total = N * K;
