@@ -165,7 +165,7 @@ def main() -> int:
                 others[mode] = round(time_steps(torch, st, max(3, args.steps // 5), 2, stream) * 1e3, 2)
         extra["us_per_decode_step_other_modes"] = others
         if args.per_shape:
-            extra["per_shape"] = per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream)
+            extra["per_shape"] = per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, args.no_cpu_baseline)
 
     gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
     launch_us = ms_per_step * 1e3 / launches_step
@@ -227,10 +227,11 @@ def _graph_time(torch, stream, run, launches, reps=10):
     return e0.elapsed_time(e1) * 1e3 / (reps * launches)
 
 
-def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream):
+def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False):
     """The other BASELINE configs, one linear per launch (not the headline):
     config 1/2: each 8B shape at M = 1, 4, 16, 64, cold (walking the 32 layer copies) -- and M = 1 hot;
-    config 4:   70B shapes at M = 1 and 32 (hot: one copy) and prefill M = 2048 on the MFMA tile."""
+    config 4:   70B shapes at M = 1 and 32 (hot: one copy) and prefill M = 2048 on the MFMA tile;
+    plus the quantizer (ptqtp_quantize) on two 8B shapes, with the oracle quantizer timed on a 256 x 4096 sample."""
     import workloads
     res = {"8b": {}, "70b": {}}
     dev = xs[0].device
@@ -261,6 +262,29 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream):
                     ent["TFLOPs"] = round(4.0 * M * n * k / us / 1e6, 1)      # two planes: 2*2*M*N*K
                 res["70b"][f"{name}_{n}x{k}_M{M}"] = ent
             del blob
+        # the step before the path: PTQTP decomposition of Gaussian fp16 weights (paper settings: T_max 50, eps 1e-4)
+        res["quantize"] = {}
+        for name in ("q", "gate"):
+            n, k = workloads.SHAPES_8B[name]
+            W = (torch.randn(n, k, device=dev) * 0.02).half()
+            ptq.ptqtp_quantize(W)
+            stream.synchronize()
+            t0 = time.perf_counter()
+            out = ptq.ptqtp_quantize(W)
+            stream.synchronize()
+            dt = time.perf_counter() - t0
+            it = int(out[4].item())
+            res["quantize"][f"{name}_{n}x{k}"] = {"ms": round(dt * 1e3, 2), "iters": it, "us_per_iter": round(dt * 1e6 / it, 1),
+                                                  "state_GBps": round(6.0 * n * k * it / dt / 1e9, 1)}
+    if not no_cpu:
+        import numpy as np
+        import oracle
+        Wh = (np.random.default_rng(1).standard_normal((256, 4096)) * 0.02).astype(np.float16)
+        t0 = time.perf_counter()
+        q = oracle.quantize(Wh)
+        dt = time.perf_counter() - t0
+        res["quantize"]["cpu_oracle_256x4096"] = {"ms": round(dt * 1e3, 1), "iters": q["iters"], "cores": 1,
+                                                  "ns_per_weight_iter": round(dt * 1e9 / (256 * 4096 * q["iters"]), 2)}
     return res
 
 
