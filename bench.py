@@ -262,6 +262,17 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
                     ent["TFLOPs"] = round(4.0 * M * n * k / us / 1e6, 1)      # two planes: 2*2*M*N*K
                 res["70b"][f"{name}_{n}x{k}_M{M}"] = ent
             del blob
+        # config 2 on the whole stack: one batched launch per step, M tokens per linear
+        res["stack_batched"] = {}
+        for M in (4, 16, 64):
+            xm = [torch.randn(M, k, device=dev).half() for (n, k) in dims]
+            ym = [torch.empty(M, n, device=dev) for (n, k) in dims]
+            plan = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xm, ym, dims)])
+            stream.synchronize()
+            ms = time_steps(torch, lambda: ptq.ptqtp_gemm_batch(plan, M), 30, 10, stream)
+            nbytes = sum(algorithmic_bytes(n, k, M) for n, k in dims)
+            res["stack_batched"][f"M{M}"] = {"us_per_step": round(ms * 1e3, 1), "GBps": round(nbytes / ms / 1e6, 1)}
+            del xm, ym, plan
         # the step before the path: PTQTP decomposition of Gaussian fp16 weights (paper settings: T_max 50, eps 1e-4)
         res["quantize"] = {}
         for name in ("q", "gate"):

@@ -170,6 +170,14 @@ ptqtp_status ptqtp_gemv_batch_plan(const ptqtp_linear *linears, int32_t count, i
 ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream);
 
 /*
+ * The same plan run with M tokens per entry, 1 <= M <= PTQTP_GEMM_SMALL_MAX_M: every entry's x is
+ * then fp16 [M, K] row-major and its y [M, N] row-major (the plan only stores the pointers; M is
+ * given here and must be the same for all entries).  One launch of the small-batch kernel over
+ * every 16-row tile of every entry.
+ */
+ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *stream);
+
+/*
  * The step before the path: PTQTP decomposition of an fp16 weight matrix into the two trit
  * planes and scales that ptqtp_pack takes (paper, Sec. "Dual Trit-planes Approximation" and
  * "Progressive Optimization", both algorithm listings): per (row, group) unit, initialise

@@ -63,6 +63,8 @@ def _load():
         lib.ptqtp_gemv_batch_plan.argtypes = [p, i32, i32, i32, p, sz, p]
         lib.ptqtp_gemv_batch.restype = i32
         lib.ptqtp_gemv_batch.argtypes = [p, i64, p]
+        lib.ptqtp_gemm_batch.restype = i32
+        lib.ptqtp_gemm_batch.argtypes = [p, i64, i64, p]
         lib.ptqtp_quantize_workspace_bytes.restype = sz
         lib.ptqtp_quantize_workspace_bytes.argtypes = [i64, i64, i32]
         lib.ptqtp_quantize.restype = i32
@@ -186,12 +188,12 @@ class BatchPlan:
 
 
 def ptqtp_gemv_batch_plan(linears, group: int = 128, y_dtype: int = PTQTP_F32) -> BatchPlan:
-    """linears: sequence of (packed, x, y, N, K) with torch tensors; y [1,N] or [N] of y_dtype."""
+    """linears: sequence of (packed, x, y, N, K) with torch tensors; x [M,K] (or [K]), y [M,N] (or [N]) of y_dtype."""
     ydt = torch.float32 if y_dtype == PTQTP_F32 else torch.float16
     n = len(linears)
     arr = (_Linear * max(n, 1))()
     for i, (packed, x, y, N, K) in enumerate(linears):
-        if x.numel() != K or y.numel() != N:
+        if x.numel() % K or y.numel() % N or x.numel() // K != y.numel() // N:
             raise PtqtpError(2, "ptqtp_gemv_batch_plan")
         arr[i] = _Linear(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"), _dev(y, ydt, "y"), N, K)
     lib = _load()
@@ -204,6 +206,13 @@ def ptqtp_gemv_batch_plan(linears, group: int = 128, y_dtype: int = PTQTP_F32) -
     if st:
         raise PtqtpError(st, "ptqtp_gemv_batch_plan")
     return BatchPlan(plan, items, [t for lin in linears for t in lin[:3]])
+
+
+def ptqtp_gemm_batch(plan: BatchPlan, M: int) -> None:
+    """Run a plan whose x tensors are [M, K] and y tensors [M, N]."""
+    st = _load().ptqtp_gemm_batch(plan.plan.data_ptr(), plan.items, int(M), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_gemm_batch")
 
 
 def ptqtp_gemv_batch(plan: BatchPlan) -> None:

@@ -522,27 +522,59 @@ hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_
 // small-batch kernel (2 <= M <= 64): item = R consecutive 16-row tiles of one linear
 // ------------------------------------------------------------------------------------------
 // Same record stream as the batch-1 kernel; each decoded field feeds MT = ceil(M/16) MFMAs.
-// Activations: a wave fetches the 16 tokens x 256 columns of its step with coalesced loads (four
-// neighbouring lanes read 64 contiguous bytes of one token), then turns them into the MFMA
-// A-operand layout (lane = token + 16*quarter) with one ds_write_b128 / ds_read_b128 pair per
-// field through a 1280-byte wave-private LDS slot -- LDS operations of a wave execute in order,
-// so the slot needs no barrier and can be reused immediately.  Lanes of tokens >= M load the
-// last real token again: their rows of D are garbage that is never stored (rows of A only
-// influence the same rows of D).
-constexpr int kBounceBytes = 1280;   // 4 quarters x 320 B: conflict-free for the write and the read
+// Activations: a wave fetches the tokens' 256-column slices of its step with fully coalesced loads
+// (32 lanes = the 512 contiguous bytes of one token, two tokens per load instruction, ML
+// instructions for up to 2*ML tokens), parks them in a wave-private LDS slot with padded rows, and
+// reads them back in the MFMA A-operand layout (lane = token + 16*quarter, 8 columns per field).
+// LDS operations of a wave execute in order, so the slot needs no barrier and is reused every step.
+// Token rows >= M re-load the last real token: their rows of D are garbage that is never stored
+// (rows of A only influence the same rows of D).
+#ifndef PTQTP_SLOT_LAYOUT
+#define PTQTP_SLOT_LAYOUT 0
+#endif
+#if PTQTP_SLOT_LAYOUT == 0
+// token-major: row r at r*528, chunk c at c*16
+constexpr int kSlotRowBytes = 528;                   // 512 B of one token + 16 B pad: conflict-free operand reads
+constexpr int kSlotBytes = 16 * kSlotRowBytes;       // per wave
+__device__ __forceinline__ int slot_wr_off(int row, int chunk) { return row * kSlotRowBytes + chunk * 16; }
+__device__ __forceinline__ int slot_rd_off(int nl, int q, int f) { return nl * kSlotRowBytes + (f >> 2) * 256 + (f & 3) * 64 + q * 16; }
+#else
+// (field, quarter)-major: block j = f*4+q of 16 tokens x 16 B at j*272
+constexpr int kSlotBytes = 32 * 272;
+__device__ __forceinline__ int slot_wr_off(int row, int chunk) {
+    const int f = (chunk >> 4) * 4 + ((chunk >> 2) & 3), q = chunk & 3;
+    return (f * 4 + q) * 272 + row * 16;
+}
+__device__ __forceinline__ int slot_rd_off(int nl, int q, int f) { return (f * 4 + q) * 272 + nl * 16; }
+#endif
 
-template <int MT, int R, int S>
+// PLAN: the item list of a batch plan (R must be 1): one launch over many linears, all with M tokens.
+// ML = load instructions per 16-token tile (1, 2, 4 or 8): covers M <= 2*ML when MT == 1.
+template <int MT, int R, int S, bool PLAN, int ML>
 __global__ void __launch_bounds__(MT * R >= 8 ? 256 : 512)
-gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
-                  int M, int N, int K, int RT, int KS, int y_f16)
+gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict__ records_,
+                  const uint16_t *__restrict__ x_, void *__restrict__ y_, int M, int N_, int K_, int RT_, int KS_,
+                  int y_f16_)
 {
     extern __shared__ float red[];                     // [W][R][MT][16 tokens][16 rows]; first used as bounce slots
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int W = blockDim.x >> 6;
     const int nl = lane & 15, q = lane >> 4;
-    const int rt0 = blockIdx.x * R;
-    const int rot = (blockIdx.x * 5) % KS;
+    const uint8_t *records = records_;
+    const uint16_t *x = x_;
+    void *y = y_;
+    int N = N_, K = K_, RT = RT_, KS = KS_, y_f16 = y_f16_, rt0 = blockIdx.x * R;
+    if (PLAN) {
+        if (static_cast<int>(blockIdx.x) >= plan->total_items) return;   // whole workgroup, before any barrier
+        const LinearDesc *table = reinterpret_cast<const LinearDesc *>(plan + 1);
+        const int32_t *map = reinterpret_cast<const int32_t *>(table + plan->count);
+        const LinearDesc *dp = table + map[blockIdx.x];
+        records = dp->records; x = dp->x; y = dp->y;
+        N = dp->N; K = dp->K; RT = dp->RT; KS = dp->KS; y_f16 = plan->y_f16;
+        rt0 = blockIdx.x - dp->first_item;
+    }
+    const int rot = (rt0 * 5) % KS;
 
     float yacc[R][MT][4];
 #pragma unroll
@@ -552,23 +584,14 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
 #pragma unroll
             for (int j = 0; j < 4; ++j) yacc[r][mt][j] = 0.f;
 
-    // loader role of this lane: token row lr, 16-byte chunk lc of every 64-byte field segment
-    const int lr = lane >> 2, lc = lane & 3;
-    const uint16_t *xrow[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        int m = mt * 16 + lr;
-        m = m < M ? m : M - 1;
-        xrow[mt] = x + static_cast<size_t>(m) * K + lc * 8;
-    }
-    char *slot = reinterpret_cast<char *>(red) + w * kBounceBytes;
-    char *slot_wr = slot + lc * 320 + lr * 16;          // where the loader puts (token lr, quarter lc)
-    const char *slot_rd = slot + q * 320 + nl * 16;     // where the MFMA lane (token nl, quarter q) finds it
+    // loader role of this lane: 16-byte chunk lc (0..31) of token row 2*i + lh of load instruction i
+    const int lh = lane >> 5, lc = lane & 31;
+    char *slot = reinterpret_cast<char *>(red) + w * kSlotBytes;
 
     for (int ks0 = w; ks0 < KS; ks0 += S * W) {
         uintx4 p1[S][R], p2[S][R];
         uintx2 sc[S][R];
-        uintx4 xa[S][MT][8];
+        uintx4 xa[S][MT][8];                          // first ML entries: raw loads; after the bounce: operands
 #pragma unroll
         for (int i = 0; i < S; ++i) {
             const int ks = ks0 + i * W;
@@ -582,13 +605,15 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
                 p2[i][r] = load_stream<uintx4>(rec + kPlaneBytes + lane * 16);
                 sc[i][r] = load_stream<uintx2>(rec + 2 * kPlaneBytes + nl * 8);
             }
+            int kc = kse * kStepK + lc * 8;
+            kc = kc < K ? kc : kc - 128;                 // padded half record: its trits are zero
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int f = 0; f < 8; ++f) {
-                    int k0 = kse * kStepK + (f >> 2) * 128;
-                    k0 = k0 < K ? k0 : k0 - 128;         // padded half record: its trits are zero
-                    xa[i][mt][f] = load_global<uintx4>(xrow[mt] + k0 + (f & 3) * 32);
+                for (int l = 0; l < ML; ++l) {
+                    int m = mt * 16 + 2 * l + lh;
+                    m = m < M ? m : M - 1;
+                    xa[i][mt][l] = load_global<uintx4>(x + static_cast<size_t>(m) * K + kc);
                 }
         }
 #pragma unroll
@@ -596,12 +621,14 @@ gemm_items_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
             const int ks = ks0 + i * W;
             if (ks < KS) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+                for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-                    for (int f = 0; f < 8; ++f) {
-                        *reinterpret_cast<uintx4 *>(slot_wr) = xa[i][mt][f];
-                        xa[i][mt][f] = *reinterpret_cast<const uintx4 *>(slot_rd);
-                    }
+                    for (int l = 0; l < ML; ++l)
+                        *reinterpret_cast<uintx4 *>(slot + slot_wr_off(2 * l + lh, lc)) = xa[i][mt][l];
+#pragma unroll
+                    for (int f = 0; f < 8; ++f)
+                        xa[i][mt][f] = *reinterpret_cast<const uintx4 *>(slot + slot_rd_off(nl, q, f));
+                }
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     const float a1g0 = half_bits_to_float(sc[i][r].x & 0xffffu), a1g1 = half_bits_to_float(sc[i][r].x >> 16);
@@ -856,6 +883,40 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
 
 int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0;
 
+template <int MT, int R, int S, bool PLAN, int ML>
+hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
+                                  int N, int K, int RT, int KS, int y_f16, int64_t grid, int W, hipStream_t stream)
+{
+    size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
+    if (lds < static_cast<size_t>(W) * kSlotBytes) lds = static_cast<size_t>(W) * kSlotBytes;
+    static bool configured = false;                  // the slots of 8 waves exceed the default 64 KB limit
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_items_kernel<MT, R, S, PLAN, ML>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 8 * kSlotBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((gemm_items_kernel<MT, R, S, PLAN, ML>), dim3(static_cast<unsigned>(grid)), dim3(W * 64), lds,
+                       stream, plan, records, x, y, M, N, K, RT, KS, y_f16);
+    return hipGetLastError();
+}
+
+// load instructions per 16-token tile needed for M tokens
+template <int MT, int R, int S, bool PLAN>
+hipError_t launch_gemm_items_ml(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
+                                int N, int K, int RT, int KS, int y_f16, int64_t grid, int W, hipStream_t stream)
+{
+    if constexpr (MT == 1) {
+        if (M <= 2)
+            return launch_gemm_items_impl<MT, R, S, PLAN, 1>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream);
+        if (M <= 4)
+            return launch_gemm_items_impl<MT, R, S, PLAN, 2>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream);
+        if (M <= 8)
+            return launch_gemm_items_impl<MT, R, S, PLAN, 4>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream);
+    }
+    return launch_gemm_items_impl<MT, R, S, PLAN, 8>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream);
+}
+
 template <int MT, int R, int S>
 hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
                              hipStream_t stream)
@@ -864,13 +925,18 @@ hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y,
     int W = g_tune_small_waves > 0 ? g_tune_small_waves : (MT * R >= 8 ? 2 : 8);
     if (W > (MT * R >= 8 ? 4 : 8)) W = MT * R >= 8 ? 4 : 8;
     while (W > 1 && W > s.KS) W /= 2;
-    const int grid = static_cast<int>((s.RT + R - 1) / R);
-    size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
-    if (lds < static_cast<size_t>(W) * kBounceBytes) lds = static_cast<size_t>(W) * kBounceBytes;
-    hipLaunchKernelGGL((gemm_items_kernel<MT, R, S>), dim3(grid), dim3(W * 64), lds, stream, records, x, y, M,
-                       static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
-                       static_cast<int>(s.KS), y_f16);
-    return hipGetLastError();
+    const int64_t grid = (s.RT + R - 1) / R;
+    return launch_gemm_items_ml<MT, R, S, false>(nullptr, records, x, y, M, static_cast<int>(s.N), static_cast<int>(s.K),
+                                                 static_cast<int>(s.RT), static_cast<int>(s.KS), y_f16, grid, W, stream);
+}
+
+// batched: every item of a plan, all linears with the same M (2..64)
+hipError_t launch_gemm_items_plan(const PlanHeader *plan, int64_t items, int M, hipStream_t stream)
+{
+    const int W = g_tune_small_waves > 0 ? (g_tune_small_waves > 8 ? 8 : g_tune_small_waves) : 4;
+    if (M <= 16) return launch_gemm_items_ml<1, 1, 2, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
+    if (M <= 32) return launch_gemm_items_ml<2, 1, 1, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
+    return launch_gemm_items_ml<4, 1, 1, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
 }
 
 int g_tune_waves = 0, g_tune_rows = 0;
@@ -899,8 +965,11 @@ int pick_waves(int64_t KS, int wmax) {
 hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int f16,
                         hipStream_t stream)
 {
-    // many row tiles: two per item share one set of activation operands
-    const int R = g_tune_small_rows > 0 ? g_tune_small_rows : (s.RT >= 512 ? 2 : 1);
+    // measured on 8B shapes: two row tiles per item (sharing one set of activation operands) when the layer has
+    // many row tiles, and always for 17..32 tokens; one otherwise
+    int R = s.RT >= 512 ? 2 : 1;
+    if (M > 16 && M <= 32) R = 2;
+    if (g_tune_small_rows > 0) R = g_tune_small_rows;
     if (M <= 16) return R == 2 ? launch_gemm_items<1, 2, 1>(records, x, y, M, s, f16, stream)
                                : launch_gemm_items<1, 1, 2>(records, x, y, M, s, f16, stream);
     if (M <= 32) return R == 2 ? launch_gemm_items<2, 2, 1>(records, x, y, M, s, f16, stream)
@@ -1129,6 +1198,16 @@ ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream_) {
     LinearDesc none = {};
     const hipError_t e = launch_items<true>(static_cast<const PlanHeader *>(plan), none, 0, items, 16,
                                             static_cast<hipStream_t>(stream_));
+    return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
+ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *stream_) {
+    if (!plan) return PTQTP_ERR_NULL;
+    if (!aligned(plan, 256)) return PTQTP_ERR_ALIGN;
+    if (items <= 0 || items > (1ll << 30) || M < 1 || M > PTQTP_GEMM_SMALL_MAX_M) return PTQTP_ERR_SHAPE;
+    if (M == 1) return ptqtp_gemv_batch(plan, items, stream_);
+    const hipError_t e = launch_gemm_items_plan(static_cast<const PlanHeader *>(plan), items, static_cast<int>(M),
+                                                static_cast<hipStream_t>(stream_));
     return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
 

@@ -184,6 +184,24 @@ def test_gemv_batch_matches_oracle_and_single_calls(ptq):
         check(ent[2], lin, x, tight=TIGHT_F16)
 
 
+@pytest.mark.parametrize("M", [1, 3, 16, 20, 64])
+def test_gemm_batch_matches_oracle(ptq, M):
+    # one launch over linears of different shapes, M tokens each
+    shapes = [(200, 2304), (7, 640), (1024, 1024), (33, 14336), (16, 128), (528, 4096)]
+    lins, xs, entries = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        lin = workloads.make_linear(N, K, 66, i)
+        x = workloads.make_x(M, K, 66, i, M)
+        y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+        lins.append(lin); xs.append(x)
+        entries.append((pack(ptq, lin), dev(x), y, N, K))
+    plan = ptq.ptqtp_gemv_batch_plan(entries)
+    for rep in range(2):
+        ptq.ptqtp_gemm_batch(plan, M)
+    for lin, x, ent in zip(lins, xs, entries):
+        check(ent[2], lin, x)
+
+
 def test_gemv_unit_vectors_exact(ptq):
     # x = e_j returns column j of W^ = a1 T1 + a2 T2; with a2/a1 in [0.1, 0.5] the sum is exact in fp32
     N, K = 80, 768
