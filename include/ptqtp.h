@@ -151,7 +151,7 @@ ptqtp_status ptqtp_gemm(const void *packed, const uint16_t *x, void *y, int32_t 
  *   plan        device, receives ptqtp_batch_plan_bytes(linears,count,group) bytes,
  *               256-byte aligned
  * ptqtp_gemv_batch runs the plan: `items` must be ptqtp_batch_items(...) of the same
- * list (= sum over entries of ceil(N/16), the number of workgroups).  The plan may be
+ * list (= sum over entries of ceil(N/16) rounded up to a multiple of 8).  The plan may be
  * re-run any number of times and stays valid while the buffers it names are alive.
  * ptqtp_batch_plan_bytes and ptqtp_batch_items return 0 for invalid arguments.
  */
@@ -210,7 +210,9 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
  * "stream_waves" (waves per item, 1..16), "stream_depth" (records in flight per
  * wave: 1, 2 or 4), "small_items" (batch > 1: 1 = item kernel, 0 = tiled kernel,
  * -1 = default), "small_waves" (waves per item for batch > 1, 1..8), "tile"
- * (1 = use the MFMA tile for every batch > 1, -1 = default);
+ * (1 = use the MFMA tile for every batch > 1, -1 = default), "small_rows" (row tiles per item of
+ * the small-batch kernel, 1 or 2), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation
+ * loads, -1/1 = shared activation tile);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
  * unknown key or out-of-range value.  Not thread-safe.
  */

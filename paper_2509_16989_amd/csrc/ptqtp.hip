@@ -429,6 +429,7 @@ gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int si
     }
     const int K = dp->K, KS = dp->KS, N = dp->N;
     const int rt = item - dp->first_item;
+    if (rt >= dp->RT) return;                       // padding item of a plan (whole workgroup leaves)
     const uint8_t *rec0 = dp->records + static_cast<size_t>(rt) * KS * kRecordBytes;
     const int rot = (rt * 5) % KS;
     const uint16_t *x = dp->x;
@@ -573,6 +574,7 @@ gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict
         records = dp->records; x = dp->x; y = dp->y;
         N = dp->N; K = dp->K; RT = dp->RT; KS = dp->KS; y_f16 = plan->y_f16;
         rt0 = blockIdx.x - dp->first_item;
+        if (rt0 >= RT) return;                       // padding item
     }
     const int rot = (rt0 * 5) % KS;
 
@@ -881,7 +883,7 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     return hipGetLastError();
 }
 
-int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0;
+int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1;
 
 template <int MT, int R, int S, bool PLAN, int ML>
 hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
@@ -937,6 +939,180 @@ hipError_t launch_gemm_items_plan(const PlanHeader *plan, int64_t items, int M, 
     if (M <= 16) return launch_gemm_items_ml<1, 1, 2, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
     if (M <= 32) return launch_gemm_items_ml<2, 1, 1, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
     return launch_gemm_items_ml<4, 1, 1, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
+}
+
+// ------------------------------------------------------------------------------------------
+// small-batch kernel for batched launches: workgroup = four row tiles sharing one activation tile
+// ------------------------------------------------------------------------------------------
+// Wave w owns row tile 4*group + w over the whole K; per 256-column step the workgroup loads the
+// step's activations once (MT*16 tokens x 512 B, coalesced, into a double-buffered LDS tile with
+// padded rows; one barrier per step) and every wave reads its MFMA A operands from there, so the
+// activation traffic through L1 is a quarter of the per-wave scheme and no cross-wave reduction
+// is needed: each wave stores its own 16 rows.  Needs four row tiles of the same linear per
+// workgroup (eight when a wave owns two), which batch plans guarantee (items are padded to a
+// multiple of eight per linear).
+template <int MT, int RTW>
+__global__ void __launch_bounds__(256)
+gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
+{
+    extern __shared__ char xtile[];                  // [2][MT*16][528]
+    constexpr int XL = 2 * MT;                       // 16-byte loads per thread per step (8 token rows per round)
+    constexpr int kBuf = MT * 16 * 528;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nl = lane & 15, q = lane >> 4;
+    const int item0 = blockIdx.x * (4 * RTW);
+    if (item0 >= plan->total_items) return;
+    const LinearDesc *table = reinterpret_cast<const LinearDesc *>(plan + 1);
+    const int32_t *map = reinterpret_cast<const int32_t *>(table + plan->count);
+    const LinearDesc *dp = table + map[item0];
+    const int N = dp->N, K = dp->K, RT = dp->RT, KS = dp->KS, y_f16 = plan->y_f16;
+    const int rt_first = item0 - dp->first_item + w * RTW;      // this wave's RTW consecutive row tiles
+    const uint8_t *rec0[RTW];
+#pragma unroll
+    for (int r = 0; r < RTW; ++r) {
+        const int rt = rt_first + r < RT ? rt_first + r : RT - 1;    // past the end: shadow the last tile, store nothing
+        rec0[r] = dp->records + static_cast<size_t>(rt) * KS * kRecordBytes;
+    }
+    const uint16_t *x = dp->x;
+    const int rot = (blockIdx.x * 5) % KS;
+
+    // staging role: token row (t/32 + 8*j), 16-byte chunk t%32
+    const int srow = threadIdx.x >> 5, schunk = threadIdx.x & 31;
+    char *xdst = xtile + srow * 528 + schunk * 16;
+    const char *xop = xtile + nl * 528 + q * 16;
+
+    float yacc[RTW][MT][4];
+#pragma unroll
+    for (int r = 0; r < RTW; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) yacc[r][mt][j] = 0.f;
+
+    auto step_of = [&](int i) { int ks = i + rot; return ks >= KS ? ks - KS : ks; };
+    auto load_x = [&](uintx4 (&st)[XL], int ks) {
+        int kc = ks * kStepK + schunk * 8;
+        kc = kc < K ? kc : kc - 128;                 // padded half record: its trits are zero
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            int m = srow + 8 * j;
+            m = m < M ? m : M - 1;
+            st[j] = load_global<uintx4>(x + static_cast<size_t>(m) * K + kc);
+        }
+    };
+    auto load_rec = [&](StepRegs (&r)[RTW], int ks) {
+#pragma unroll
+        for (int t = 0; t < RTW; ++t) {
+            const uint8_t *rec = rec0[t] + static_cast<size_t>(ks) * kRecordBytes;
+            r[t].p1 = load_stream<uintx4>(rec + lane * 16);
+            r[t].p2 = load_stream<uintx4>(rec + kPlaneBytes + lane * 16);
+            r[t].sc = load_stream<uintx2>(rec + 2 * kPlaneBytes + nl * 8);
+        }
+    };
+    auto compute = [&](const StepRegs (&r)[RTW], int buf) {
+        const char *xb = xop + buf * kBuf;
+#pragma unroll
+        for (int g2 = 0; g2 < 2; ++g2) {
+            floatx4 acc1[RTW][MT], acc2[RTW][MT];
+#pragma unroll
+            for (int t = 0; t < RTW; ++t)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) { acc1[t][mt] = floatx4{0.f, 0.f, 0.f, 0.f}; acc2[t][mt] = floatx4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+            for (int fm = 0; fm < 4; ++fm) {
+                const int wi = 2 * g2 + (fm >> 1), par = fm & 1;
+                half8 b1[RTW], b2[RTW];
+#pragma unroll
+                for (int t = 0; t < RTW; ++t) { b1[t] = decode8(r[t].p1[wi], par); b2[t] = decode8(r[t].p2[wi], par); }
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const half8 a = __builtin_bit_cast(
+                        half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * 528 + g2 * 256 + fm * 64));
+#pragma unroll
+                    for (int t = 0; t < RTW; ++t) {
+                        acc1[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b1[t], acc1[t][mt], 0, 0, 0);
+                        acc2[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b2[t], acc2[t][mt], 0, 0, 0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < RTW; ++t) {
+                const float a1 = half_bits_to_float(g2 ? (r[t].sc.x >> 16) : (r[t].sc.x & 0xffffu));
+                const float a2 = half_bits_to_float(g2 ? (r[t].sc.y >> 16) : (r[t].sc.y & 0xffffu));
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        yacc[t][mt][j] = fmaf(a1, acc1[t][mt][j], yacc[t][mt][j]);
+                        yacc[t][mt][j] = fmaf(a2, acc2[t][mt][j], yacc[t][mt][j]);
+                    }
+            }
+        }
+    };
+    auto publish = [&](const uintx4 (&st)[XL], int buf) {
+        char *d = xdst + buf * kBuf;
+#pragma unroll
+        for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(d + j * 8 * 528) = st[j];
+    };
+
+    uintx4 stage[XL];
+    StepRegs ra[RTW], rb[RTW];
+    load_x(stage, step_of(0));
+    load_rec(ra, step_of(0));
+#pragma unroll
+    for (int t = 0; t < RTW; ++t) rb[t] = ra[t];
+    publish(stage, 0);
+    __syncthreads();
+    // two steps per trip so that the record registers ping-pong without copies
+    for (int i = 0; i < KS; i += 2) {
+        const bool m1 = i + 1 < KS, m2 = i + 2 < KS;
+        if (m1) { load_x(stage, step_of(i + 1)); load_rec(rb, step_of(i + 1)); }
+        compute(ra, 0);
+        if (m1) publish(stage, 1);
+        __syncthreads();
+        if (m1) {
+            if (m2) { load_x(stage, step_of(i + 2)); load_rec(ra, step_of(i + 2)); }
+            compute(rb, 1);
+            if (m2) publish(stage, 0);
+            __syncthreads();
+        }
+    }
+
+#pragma unroll
+    for (int t = 0; t < RTW; ++t) {
+        const int rt = rt_first + t;
+        const int n = rt * kTileRows + nl;
+        if (rt < RT && n < N) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int m = mt * 16 + 4 * q + j;
+                    if (m < M) {
+                        const size_t off = static_cast<size_t>(m) * N + n;
+                        if (y_f16) reinterpret_cast<_Float16 *>(dp->y)[off] = static_cast<_Float16>(yacc[t][mt][j]);
+                        else reinterpret_cast<float *>(dp->y)[off] = yacc[t][mt][j];
+                    }
+                }
+        }
+    }
+}
+
+template <int MT, int RTW>
+hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStream_t stream)
+{
+    const size_t lds = 2 * static_cast<size_t>(MT) * 16 * 528;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((gemm_rows_kernel<MT, RTW>), dim3(static_cast<unsigned>((items + 4 * RTW - 1) / (4 * RTW))),
+                       dim3(256), lds, stream, plan, M);
+    return hipGetLastError();
 }
 
 int g_tune_waves = 0, g_tune_rows = 0;
@@ -1134,7 +1310,7 @@ static ptqtp_status plan_items(const ptqtp_linear *linears, int32_t count, int32
         Shape s;
         ptqtp_status st;
         if (!make_shape(1, linears[i].N, linears[i].K, group, &s, &st)) return st;
-        *total += s.RT;
+        *total += (s.RT + 7) / 8 * 8;          // every linear starts a new group of eight items
     }
     return *total > (1ll << 30) ? PTQTP_ERR_SHAPE : PTQTP_OK;
 }
@@ -1175,7 +1351,7 @@ ptqtp_status ptqtp_gemv_batch_plan(const ptqtp_linear *linears, int32_t count, i
             d.N = static_cast<int32_t>(s.N); d.K = static_cast<int32_t>(s.K);
             d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
             d.first_item = static_cast<int32_t>(first); d.pad = 0;
-            first += s.RT;
+            first += (s.RT + 7) / 8 * 8;
         }
         hipLaunchKernelGGL(plan_write_kernel, dim3(1), dim3(64), 0, stream, static_cast<PlanHeader *>(plan), chunk,
                            base, n, count, static_cast<int>(total), y_dtype == PTQTP_F16 ? 1 : 0);
@@ -1206,8 +1382,18 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
     if (!aligned(plan, 256)) return PTQTP_ERR_ALIGN;
     if (items <= 0 || items > (1ll << 30) || M < 1 || M > PTQTP_GEMM_SMALL_MAX_M) return PTQTP_ERR_SHAPE;
     if (M == 1) return ptqtp_gemv_batch(plan, items, stream_);
-    const hipError_t e = launch_gemm_items_plan(static_cast<const PlanHeader *>(plan), items, static_cast<int>(M),
-                                                static_cast<hipStream_t>(stream_));
+    const PlanHeader *ph = static_cast<const PlanHeader *>(plan);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const int Mi = static_cast<int>(M);
+    hipError_t e;
+    if (g_tune_small_rows_kernel == 0) e = launch_gemm_items_plan(ph, items, Mi, stream);
+    // row tiles per wave, measured on the 8B stack: two up to 32 tokens, one above (registers)
+    else if (M <= 16) e = g_tune_small_rows == 1 ? launch_gemm_rows<1, 1>(ph, items, Mi, stream)
+                                                 : launch_gemm_rows<1, 2>(ph, items, Mi, stream);
+    else if (M <= 32) e = g_tune_small_rows == 1 ? launch_gemm_rows<2, 1>(ph, items, Mi, stream)
+                                                 : launch_gemm_rows<2, 2>(ph, items, Mi, stream);
+    else e = g_tune_small_rows == 2 ? launch_gemm_rows<4, 2>(ph, items, Mi, stream)
+                                    : launch_gemm_rows<4, 1>(ph, items, Mi, stream);
     return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
 
@@ -1226,6 +1412,11 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!strcmp(key, "tile")) {
         if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
         g_tune_tile = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "batch_rows_kernel")) {
+        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
+        g_tune_small_rows_kernel = value;
         return PTQTP_OK;
     }
     if (!strcmp(key, "small_rows")) {

@@ -160,7 +160,7 @@ def test_gemv_batch_matches_oracle_and_single_calls(ptq):
         entries.append((packed, xd, y, N, K))
         singles.append(ptq.ptqtp_gemv(packed, xd, N, K))
     plan = ptq.ptqtp_gemv_batch_plan(entries)
-    assert plan.items == sum((N + 15) // 16 for N, _ in shapes)
+    assert plan.items == sum(((N + 15) // 16 + 7) // 8 * 8 for N, _ in shapes)
     for rep in range(3):
         ptq.ptqtp_gemv_batch(plan)
     for lin, x, ent, y1 in zip(lins, xs, entries, singles):
@@ -196,10 +196,19 @@ def test_gemm_batch_matches_oracle(ptq, M):
         lins.append(lin); xs.append(x)
         entries.append((pack(ptq, lin), dev(x), y, N, K))
     plan = ptq.ptqtp_gemv_batch_plan(entries)
-    for rep in range(2):
-        ptq.ptqtp_gemm_batch(plan, M)
-    for lin, x, ent in zip(lins, xs, entries):
-        check(ent[2], lin, x)
+    for kernel, rows in ((-1, 0), (-1, 1), (-1, 2), (0, 0)):   # shared activation tile (1 or 2 row tiles per wave), per-wave loads
+        try:
+            ptq.ptqtp_tune("batch_rows_kernel", kernel)
+            ptq.ptqtp_tune("small_rows", rows)
+            for ent in entries:
+                ent[2].fill_(float("nan"))
+            for rep in range(2):
+                ptq.ptqtp_gemm_batch(plan, M)
+        finally:
+            ptq.ptqtp_tune("batch_rows_kernel", -1)
+            ptq.ptqtp_tune("small_rows", 0)
+        for lin, x, ent in zip(lins, xs, entries):
+            check(ent[2], lin, x)
 
 
 def test_gemv_unit_vectors_exact(ptq):
