@@ -83,6 +83,25 @@ def make_step(ptq, torch, mode, blobs, xs, ys, dims, stream):
         with torch.cuda.graph(graph, stream=stream):
             run_calls()
         return graph.replay, len(blobs)
+    if mode == "fused4":
+        # what a real decode step can fuse without breaking dependencies: {q,k,v}, {o}, {gate,up}, {down} per layer
+        ents = [(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xs, ys, dims)]
+        plans = []
+        for layer in range(len(blobs) // 7):
+            e = ents[7 * layer:7 * layer + 7]
+            plans += [ptq.ptqtp_gemv_batch_plan(e[0:3]), ptq.ptqtp_gemv_batch_plan(e[3:4]),
+                      ptq.ptqtp_gemv_batch_plan(e[4:6]), ptq.ptqtp_gemv_batch_plan(e[6:7])]
+
+        def run_plans():
+            for p in plans:
+                ptq.ptqtp_gemv_batch(p)
+        run_plans()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run_plans()
+        graph._keep = plans
+        return graph.replay, len(plans)
     plan = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xs, ys, dims)])
     stream.synchronize()
     return (lambda: ptq.ptqtp_gemv_batch(plan)), 1
@@ -112,9 +131,11 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--layers", type=int, default=32)
-    ap.add_argument("--mode", choices=["batch", "graph", "eager"], default="batch",
-                    help="batch: one ptqtp_gemv_batch launch per step; graph: 7*layers ptqtp_gemv launches "
-                         "replayed as one hipGraph; eager: the same launches issued call by call")
+    ap.add_argument("--mode", choices=["batch", "fused4", "graph", "eager"], default="batch",
+                    help="batch: one ptqtp_gemv_batch launch per step; fused4: 4 batched launches per layer "
+                         "({q,k,v},{o},{gate,up},{down}: what a dependent decode step can fuse) replayed as one hipGraph; "
+                         "graph: 7*layers ptqtp_gemv launches replayed as one hipGraph; eager: the same launches issued "
+                         "call by call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run 5 plain 1 GiB device copies (known HBM traffic) and exit: the reference that "
@@ -159,7 +180,7 @@ def main() -> int:
         step, launches_step = make_step(ptq, torch, args.mode, blobs, xs, ys, dims, stream)
         ms_per_step = time_steps(torch, step, args.steps, args.warmup, stream)
         others = {}
-        for mode in ("batch", "graph"):
+        for mode in ("batch", "fused4", "graph"):
             if mode != args.mode:
                 st, _ = make_step(ptq, torch, mode, blobs, xs, ys, dims, stream)
                 others[mode] = round(time_steps(torch, st, max(3, args.steps // 5), 2, stream) * 1e3, 2)

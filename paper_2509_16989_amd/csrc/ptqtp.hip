@@ -505,7 +505,7 @@ hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_
     // A batched launch has thousands of items in flight: 4 waves x 2 records each is enough.  A single
     // linear has few items, so more waves per item put the whole matrix in flight at once.
     int W = 4, S = 2;
-    if (!PLAN) {
+    if (!PLAN || total_items < 2048) {
         S = 1;
         while (W < 16 && total_items * W * 2 <= 4096) W *= 2;
         while (W > 1 && W > min_ks) W /= 2;
