@@ -861,6 +861,175 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     }
 }
 
+// Variant with two waves per SIMD: workgroup = 2 x 2 waves, each 4 row tiles x 4 token tiles
+// (128 rows x 128 tokens per workgroup), the record words of a scale group fetched just in time
+// (8 bytes per lane, plane and row tile) so that a wave fits in 256 registers and two workgroups
+// share a CU: while one waits at its barrier the other keeps the matrix pipe busy.
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+gemm_tile2_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
+                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB)
+{
+    extern __shared__ char xt[];                     // [2][128][kTileXStride]
+    constexpr int TM = 128, NRT = 8, XL = 8;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nl = lane & 15, q = lane >> 4;
+    const int wm = w & 1, wn = w >> 1;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int nb = (slot / MB) * 8 + xcd, mb = slot % MB;
+    if (nb >= NB) return;                            // whole workgroup, before any barrier
+    const int m0 = mb * TM;
+    const int rt_base = nb * NRT + wn * 4;
+    const int NG = K / 128;
+
+    const int srow = threadIdx.x >> 4, schunk = threadIdx.x & 15;
+    const uint16_t *xsrc[XL];
+#pragma unroll
+    for (int j = 0; j < XL; ++j) {
+        int m = m0 + srow + 16 * j;
+        m = m < M ? m : M - 1;
+        xsrc[j] = x + static_cast<size_t>(m) * K + schunk * 8;
+    }
+    char *xdst = xt + srow * kTileXStride + schunk * 16;
+    const char *xop = xt + (wm * 64 + nl) * kTileXStride + q * 16;
+
+    const uint8_t *rec[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        int rt = rt_base + r;
+        rt = rt < RT ? rt : RT - 1;
+        rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes + lane * 16;
+    }
+
+    floatx4 acc[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // words of group g: record g/2, half g%2 -> 8 bytes per lane, plane and row tile; scales: 4 fp16 per row
+    auto load_group = [&](uintx2 (&pw)[4][2], uintx2 (&sc)[4], int g) {
+        const size_t off = static_cast<size_t>(g >> 1) * kRecordBytes + (g & 1) * 8;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            pw[r][0] = load_global<uintx2>(rec[r] + off);
+            pw[r][1] = load_global<uintx2>(rec[r] + off + kPlaneBytes);
+            sc[r] = load_global<uintx2>(rec[r] - lane * 16 + static_cast<size_t>(g >> 1) * kRecordBytes + 2 * kPlaneBytes + nl * 8);
+        }
+    };
+    auto compute = [&](const uintx2 (&pw)[4][2], const uintx2 (&sc)[4], int g) {
+        const char *xb = xop + (g & 1) * (TM * kTileXStride);
+        const int h = g & 1;
+        half8 al[4][2];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].x >> 16) : (sc[r].x & 0xffffu)));
+            const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].y >> 16) : (sc[r].y & 0xffffu)));
+            al[r][0] = half8{a1, a1, a1, a1, a1, a1, a1, a1};
+            al[r][1] = half8{a2, a2, a2, a2, a2, a2, a2, a2};
+        }
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm) {
+            half8 b[2][4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int pl = 0; pl < 2; ++pl)
+                    b[pl][r] = decode8((fm >> 1) ? pw[r][pl].y : pw[r][pl].x, fm & 1) * al[r][pl];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                const half8 a = __builtin_bit_cast(
+                    half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * kTileXStride + fm * 64));
+#pragma unroll
+                for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[pl][r], acc[r][mt], 0, 0, 0);
+            }
+        }
+    };
+
+    uintx4 stage[XL];
+    uintx2 pa[4][2], pb[4][2], sa[4], sb[4];
+#pragma unroll
+    for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j]);
+    load_group(pa, sa, 0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { pb[r][0] = pa[r][0]; pb[r][1] = pa[r][1]; sb[r] = sa[r]; }
+#pragma unroll
+    for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(xdst + j * 16 * kTileXStride) = stage[j];
+    __syncthreads();
+
+    for (int g = 0; g < NG; g += 2) {
+        const bool m1 = g + 1 < NG, m2 = g + 2 < NG;
+        if (m1) {
+#pragma unroll
+            for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j] + (g + 1) * 128);
+            load_group(pb, sb, g + 1);
+        }
+        compute(pa, sa, g);
+        if (m1) {
+            char *d = xdst + TM * kTileXStride;
+#pragma unroll
+            for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(d + j * 16 * kTileXStride) = stage[j];
+        }
+        __syncthreads();
+        if (m1) {
+            if (m2) {
+#pragma unroll
+                for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j] + (g + 2) * 128);
+                load_group(pa, sa, g + 2);
+            }
+            compute(pb, sb, g + 1);
+            if (m2) {
+#pragma unroll
+                for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(xdst + j * 16 * kTileXStride) = stage[j];
+            }
+            __syncthreads();
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int rt = rt_base + r;
+        const int n = rt * kTileRows + nl;
+        if (rt < RT && n < N) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int m = m0 + wm * 64 + mt * 16 + 4 * q + j;
+                    if (m < M) {
+                        const size_t off = static_cast<size_t>(m) * N + n;
+                        if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(acc[r][mt][j]);
+                        else reinterpret_cast<float *>(y)[off] = acc[r][mt][j];
+                    }
+                }
+        }
+    }
+}
+
+hipError_t launch_gemm_tile2(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
+                             hipStream_t stream)
+{
+    constexpr int TM = 128, NRT = 8;
+    const int MB = (M + TM - 1) / TM;
+    const int NB = static_cast<int>((s.RT + NRT - 1) / NRT);
+    const int64_t grid = static_cast<int64_t>((NB + 7) / 8) * 8 * MB;
+    const size_t lds = 2 * static_cast<size_t>(TM) * kTileXStride;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile2_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(gemm_tile2_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x, y, M,
+                       static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT), static_cast<int>(s.KS),
+                       y_f16, MB, NB);
+    return hipGetLastError();
+}
+
 template <int MTW>
 hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
                             hipStream_t stream)
@@ -883,7 +1052,7 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     return hipGetLastError();
 }
 
-int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1;
+int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0;
 
 template <int MT, int R, int S, bool PLAN, int ML>
 hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
@@ -1182,7 +1351,11 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
         else if (R >= 2) e = launch_gemv<1, 2, true>(records, x, y, Mi, s, W, f16, stream);
         else e = launch_gemv<1, 1, true>(records, x, y, Mi, s, W, f16, stream);
     } else if (M >= 256 || g_tune_tile == 1) {
-        if (M <= 64) e = launch_gemm_tile<4>(records, x, y, Mi, s, f16, stream);
+        // 256-row x 128-token tiles leave CUs idle on small problems: use the 128 x 128 variant then
+        const int64_t big_tiles = ((s.RT + 15) / 16) * ((M + 127) / 128);
+        if (g_tune_tile_variant == 2 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && big_tiles < 256))
+            e = launch_gemm_tile2(records, x, y, Mi, s, f16, stream);
+        else if (M <= 64) e = launch_gemm_tile<4>(records, x, y, Mi, s, f16, stream);
         else e = launch_gemm_tile<8>(records, x, y, Mi, s, f16, stream);
     } else if (M > PTQTP_GEMM_SMALL_MAX_M) {
         // 65..255 tokens: too few token blocks to fill the chip with 256-row tiles; run the
@@ -1407,6 +1580,11 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!strcmp(key, "stream_waves")) {
         if (value < 0 || value > 16) return PTQTP_ERR_SHAPE;
         g_tune_stream_waves = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "tile_variant")) {
+        if (value != 0 && value != 2) return PTQTP_ERR_SHAPE;
+        g_tune_tile_variant = value;
         return PTQTP_OK;
     }
     if (!strcmp(key, "tile")) {
