@@ -1583,7 +1583,7 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
         return PTQTP_OK;
     }
     if (!strcmp(key, "tile_variant")) {
-        if (value != 0 && value != 2) return PTQTP_ERR_SHAPE;
+        if (value < 0 || value > 2) return PTQTP_ERR_SHAPE;
         g_tune_tile_variant = value;
         return PTQTP_OK;
     }

@@ -341,15 +341,17 @@ def test_gemm_tile_shapes(ptq, N, K, M):
 
 
 @pytest.mark.parametrize("N,K,M", [(528, 2048, 300), (200, 1024, 257), (1000, 640, 513), (16, 384, 256), (4096, 256, 400)])
-def test_gemm_tile_two_wave_variant(ptq, N, K, M):
+def test_gemm_tile_variants(ptq, N, K, M):
     lin = workloads.make_linear(N, K, 73, N, K)
     x = workloads.make_x(M, K, 73, N, M)
-    try:
-        ptq.ptqtp_tune("tile_variant", 2)
-        y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K)
-    finally:
-        ptq.ptqtp_tune("tile_variant", 0)
-    check(y, lin, x, tight=3e-5)
+    packed = pack(ptq, lin)
+    for variant in (1, 2):                         # 256 x 128 tile, 128 x 128 tile
+        try:
+            ptq.ptqtp_tune("tile_variant", variant)
+            y = ptq.ptqtp_gemm(packed, dev(x), N, K)
+        finally:
+            ptq.ptqtp_tune("tile_variant", 0)
+        check(y, lin, x, tight=3e-5)
 
 
 @pytest.mark.parametrize("M", [2, 16, 33, 64])
