@@ -220,25 +220,48 @@ quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_
             *reinterpret_cast<uintx4 *>(T2 + off + 16 * i) = uintx4{o2[4 * i], o2[4 * i + 1], o2[4 * i + 2], o2[4 * i + 3]};
         }
         if (part == 0) {
-            const double d1 = a1 - ap1, d2 = a2 - ap2;
-            const double q1 = d1 * d1, q2 = d2 * d2;
             alpha[2 * u] = a1;
             alpha[2 * u + 1] = a2;
             lambda[u] = lam;
-            delta2[u] = q1 + q2;
         }
+    }
+    // this workgroup's share of || alpha_t - alpha_(t-1) ||_F^2: its 64 units in a fixed order
+    // (wave butterfly, then the four waves in turn)
+    double dsum = 0.0;
+    if (valid && part == 0) {
+        const double d1 = a1 - ap1, d2 = a2 - ap2;
+        const double q1 = d1 * d1, q2 = d2 * d2;
+        dsum = q1 + q2;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint64_t bits = __builtin_bit_cast(uint64_t, dsum);
+        const int lo = __shfl_xor(static_cast<int>(bits & 0xffffffffu), o, 64);
+        const int hi = __shfl_xor(static_cast<int>(bits >> 32), o, 64);
+        dsum = dsum + __builtin_bit_cast(double, (static_cast<uint64_t>(static_cast<uint32_t>(hi)) << 32) | static_cast<uint32_t>(lo));
+    }
+    __shared__ double wsum[4];
+    if (lane == 0) wsum[threadIdx.x >> 6] = dsum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = wsum[0];
+        t = t + wsum[1];
+        t = t + wsum[2];
+        t = t + wsum[3];
+        delta2[blockIdx.x] = t;
     }
 }
 
-// Stopping rule: || alpha_t - alpha_(t-1) ||_F < eps over all units.  One workgroup, fixed order:
-// thread i adds elements i, i+1024, ... , then a binary tree in LDS.
+// Stopping rule: || alpha_t - alpha_(t-1) ||_F < eps over all units.  The unit kernel leaves one partial
+// sum per workgroup; here one workgroup adds them in a fixed order: thread i takes partials i, i+1024, ...,
+// then a binary tree in LDS.
 __global__ void __launch_bounds__(1024)
-quant_check_kernel(const double *__restrict__ delta2, int64_t units, double eps, QuantFlags *flags, int t)
+quant_check_kernel(const double *__restrict__ delta2, int64_t nparts, double eps, QuantFlags *flags, int t)
 {
     __shared__ double part[1024];
     if (flags->done) return;
     double s = 0.0;
-    for (int64_t i = threadIdx.x; i < units; i += 1024) s += delta2[i];
+    for (int64_t i = threadIdx.x; i < nparts; i += 1024) s += delta2[i];
     part[threadIdx.x] = s;
     __syncthreads();
     for (int o = 512; o > 0; o >>= 1) {
@@ -327,7 +350,7 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
         else
             hipLaunchKernelGGL(quant_iter_kernel<false>, dim3(ublocks), dim3(256), 0, stream, W, T1, T2, alpha, lambda,
                                delta2, flags, units, NG, K);
-        hipLaunchKernelGGL(quant_check_kernel, dim3(1), dim3(1024), 0, stream, delta2, units, eps, flags, t);
+        hipLaunchKernelGGL(quant_check_kernel, dim3(1), dim3(1024), 0, stream, delta2, static_cast<int64_t>(ublocks), eps, flags, t);
     }
     hipLaunchKernelGGL(quant_finish_kernel, dim3(static_cast<unsigned>((units + 255) / 256)), dim3(256), 0, stream, alpha,
                        a1, a2, flags, iters, units);
