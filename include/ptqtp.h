@@ -213,7 +213,9 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
  * (1 = use the MFMA tile for every batch > 1, -1 = default), "tile_variant" (1 = always the
  * 256 x 128 tile, 2 = always the 128 x 128 two-waves-per-SIMD tile, 0 = default: by problem size), "small_rows" (row tiles per item of
  * the small-batch kernel, 1 or 2), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation
- * loads, -1/1 = shared activation tile);
+ * loads, -1/1 = shared activation tile), "small_fold" (ptqtp_gemm_batch with two row tiles per wave:
+ * 1 = multiply the group scales into the expanded trits before the matrix pipe, 0 = rescale the
+ * per-group sums after it, -1 = default: before for more than 16 tokens);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
  * unknown key or out-of-range value.  Not thread-safe.
  */

@@ -1052,7 +1052,7 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     return hipGetLastError();
 }
 
-int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0;
+int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0, g_tune_small_fold = -1;
 
 template <int MT, int R, int S, bool PLAN, int ML>
 hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
@@ -1120,8 +1120,16 @@ hipError_t launch_gemm_items_plan(const PlanHeader *plan, int64_t items, int M, 
 // is needed: each wave stores its own 16 rows.  Needs four row tiles of the same linear per
 // workgroup (eight when a wave owns two), which batch plans guarantee (items are padded to a
 // multiple of eight per linear).
-template <int MT, int RTW>
-__global__ void __launch_bounds__(256)
+//
+// FOLD: the group scale is multiplied into the expanded trits before the matrix pipe
+// (alpha * {0,+-1} is exact in fp16 and alpha*t*x is exact in fp32), so both planes and all
+// groups accumulate into one set of MFMA accumulators that lives across the whole K loop:
+// no per-group accumulator reset and rescale.  Pays once a decoded operand is reused by
+// several token tiles (MT >= 2).
+// At least two waves per SIMD (at most 256 registers per lane) wherever the accumulators allow:
+// the compiler then keeps MFMA results in ordinary VGPRs and the rescale reads them in place.
+template <int MT, int RTW, bool FOLD>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((!FOLD && MT * RTW >= 8) ? 1 : 2)))
 gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
 {
     extern __shared__ char xtile[];                  // [2][MT*16][528]
@@ -1151,13 +1159,11 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
     char *xdst = xtile + srow * 528 + schunk * 16;
     const char *xop = xtile + nl * 528 + q * 16;
 
-    float yacc[RTW][MT][4];
+    floatx4 yacc[RTW][MT];
 #pragma unroll
     for (int r = 0; r < RTW; ++r)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) yacc[r][mt][j] = 0.f;
+        for (int mt = 0; mt < MT; ++mt) yacc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     auto step_of = [&](int i) { int ks = i + rot; return ks >= KS ? ks - KS : ks; };
     auto load_x = [&](uintx4 (&st)[XL], int ks) {
@@ -1181,8 +1187,44 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
     };
     auto compute = [&](const StepRegs (&r)[RTW], int buf) {
         const char *xb = xop + buf * kBuf;
+        if constexpr (FOLD) {
+            // operand reads run one 32-column field ahead of the MFMAs that use them
+            half8 a[2][MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                a[0][mt] = __builtin_bit_cast(half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * 528));
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+                const int g2 = f >> 2, fm = f & 3;
+                const int wi = 2 * g2 + (fm >> 1), par = fm & 1;
+                if (f + 1 < 8) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        a[(f + 1) & 1][mt] = __builtin_bit_cast(
+                            half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * 528 + (f + 1) * 64));
+                }
+                half8 b[2][RTW];
+#pragma unroll
+                for (int t = 0; t < RTW; ++t) {
+                    const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(g2 ? (r[t].sc.x >> 16) : (r[t].sc.x & 0xffffu)));
+                    const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(g2 ? (r[t].sc.y >> 16) : (r[t].sc.y & 0xffffu)));
+                    b[0][t] = decode8(r[t].p1[wi], par) * half8{a1, a1, a1, a1, a1, a1, a1, a1};
+                    b[1][t] = decode8(r[t].p2[wi], par) * half8{a2, a2, a2, a2, a2, a2, a2, a2};
+                }
+                // consecutive MFMAs write different accumulators
+#pragma unroll
+                for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int t = 0; t < RTW; ++t)
+                            yacc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[f & 1][mt], b[pl][t], yacc[t][mt], 0, 0, 0);
+            }
+            return;
+        }
 #pragma unroll
         for (int g2 = 0; g2 < 2; ++g2) {
+            {
             floatx4 acc1[RTW][MT], acc2[RTW][MT];
 #pragma unroll
             for (int t = 0; t < RTW; ++t)
@@ -1217,6 +1259,7 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
                         yacc[t][mt][j] = fmaf(a2, acc2[t][mt][j], yacc[t][mt][j]);
                     }
             }
+            }
         }
     };
     auto publish = [&](const uintx4 (&st)[XL], int buf) {
@@ -1241,10 +1284,10 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
         if (m1) publish(stage, 1);
         __syncthreads();
         if (m1) {
-            if (m2) { load_x(stage, step_of(i + 2)); load_rec(ra, step_of(i + 2)); }
-            compute(rb, 1);
-            if (m2) publish(stage, 0);
-            __syncthreads();
+                if (m2) { load_x(stage, step_of(i + 2)); load_rec(ra, step_of(i + 2)); }
+                compute(rb, 1);
+                if (m2) publish(stage, 0);
+                __syncthreads();
         }
     }
 
@@ -1268,18 +1311,18 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
     }
 }
 
-template <int MT, int RTW>
+template <int MT, int RTW, bool FOLD>
 hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStream_t stream)
 {
     const size_t lds = 2 * static_cast<size_t>(MT) * 16 * 528;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW, FOLD>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((gemm_rows_kernel<MT, RTW>), dim3(static_cast<unsigned>((items + 4 * RTW - 1) / (4 * RTW))),
+    hipLaunchKernelGGL((gemm_rows_kernel<MT, RTW, FOLD>), dim3(static_cast<unsigned>((items + 4 * RTW - 1) / (4 * RTW))),
                        dim3(256), lds, stream, plan, M);
     return hipGetLastError();
 }
@@ -1560,18 +1603,29 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
     const int Mi = static_cast<int>(M);
     hipError_t e;
     if (g_tune_small_rows_kernel == 0) e = launch_gemm_items_plan(ph, items, Mi, stream);
-    // row tiles per wave, measured on the 8B stack: two up to 32 tokens, one above (registers)
-    else if (M <= 16) e = g_tune_small_rows == 1 ? launch_gemm_rows<1, 1>(ph, items, Mi, stream)
-                                                 : launch_gemm_rows<1, 2>(ph, items, Mi, stream);
-    else if (M <= 32) e = g_tune_small_rows == 1 ? launch_gemm_rows<2, 1>(ph, items, Mi, stream)
-                                                 : launch_gemm_rows<2, 2>(ph, items, Mi, stream);
-    else e = g_tune_small_rows == 2 ? launch_gemm_rows<4, 2>(ph, items, Mi, stream)
-                                    : launch_gemm_rows<4, 1>(ph, items, Mi, stream);
+    else {
+        const int rows = g_tune_small_rows ? g_tune_small_rows : 2;
+        const bool fold = g_tune_small_fold < 0 ? M > 16 : g_tune_small_fold != 0;
+        if (M <= 16) e = rows == 1 ? launch_gemm_rows<1, 1, false>(ph, items, Mi, stream)
+                       : fold ? launch_gemm_rows<1, 2, true>(ph, items, Mi, stream)
+                              : launch_gemm_rows<1, 2, false>(ph, items, Mi, stream);
+        else if (M <= 32) e = rows == 1 ? launch_gemm_rows<2, 1, false>(ph, items, Mi, stream)
+                            : fold ? launch_gemm_rows<2, 2, true>(ph, items, Mi, stream)
+                                   : launch_gemm_rows<2, 2, false>(ph, items, Mi, stream);
+        else e = rows == 1 ? launch_gemm_rows<4, 1, false>(ph, items, Mi, stream)
+                 : fold ? launch_gemm_rows<4, 2, true>(ph, items, Mi, stream)
+                        : launch_gemm_rows<4, 2, false>(ph, items, Mi, stream);
+    }
     return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
 
 ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!key) return PTQTP_ERR_NULL;
+    if (!strcmp(key, "small_fold")) {
+        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
+        g_tune_small_fold = value;
+        return PTQTP_OK;
+    }
     if (!strcmp(key, "gemv_stream")) {
         if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
         g_tune_stream = value;

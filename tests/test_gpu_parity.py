@@ -184,7 +184,7 @@ def test_gemv_batch_matches_oracle_and_single_calls(ptq):
         check(ent[2], lin, x, tight=TIGHT_F16)
 
 
-@pytest.mark.parametrize("M", [1, 3, 16, 20, 64])
+@pytest.mark.parametrize("M", [1, 3, 16, 20, 40, 64])
 def test_gemm_batch_matches_oracle(ptq, M):
     # one launch over linears of different shapes, M tokens each
     shapes = [(200, 2304), (7, 640), (1024, 1024), (33, 14336), (16, 128), (528, 4096)]
@@ -196,10 +196,12 @@ def test_gemm_batch_matches_oracle(ptq, M):
         lins.append(lin); xs.append(x)
         entries.append((pack(ptq, lin), dev(x), y, N, K))
     plan = ptq.ptqtp_gemv_batch_plan(entries)
-    for kernel, rows in ((-1, 0), (-1, 1), (-1, 2), (0, 0)):   # shared activation tile (1 or 2 row tiles per wave), per-wave loads
+    # shared activation tile (1 or 2 row tiles per wave; scales applied after or before the matrix pipe), per-wave loads
+    for kernel, rows, fold in ((-1, 0, -1), (-1, 1, -1), (-1, 2, 0), (-1, 2, 1), (0, 0, -1)):
         try:
             ptq.ptqtp_tune("batch_rows_kernel", kernel)
             ptq.ptqtp_tune("small_rows", rows)
+            ptq.ptqtp_tune("small_fold", fold)
             for ent in entries:
                 ent[2].fill_(float("nan"))
             for rep in range(2):
@@ -207,6 +209,7 @@ def test_gemm_batch_matches_oracle(ptq, M):
         finally:
             ptq.ptqtp_tune("batch_rows_kernel", -1)
             ptq.ptqtp_tune("small_rows", 0)
+            ptq.ptqtp_tune("small_fold", -1)
         for lin, x, ent in zip(lins, xs, entries):
             check(ent[2], lin, x)
 
@@ -234,6 +237,30 @@ def test_integer_exact_bitwise(ptq, M):
     y_ref, _ = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
     y = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K).cpu().numpy().astype(np.float64)
     assert np.array_equal(y, y_ref)
+
+
+@pytest.mark.parametrize("M", [2, 16, 24, 48, 64])
+def test_gemm_batch_integer_exact_bitwise(ptq, M):
+    # the batched small-batch kernels (scales applied after or inside the matrix pipe) on inputs whose
+    # partial sums are all exactly representable: the oracle's bits in any summation order
+    shapes = [(208, 3072), (40, 14336), (129, 256)]
+    cases, entries = [], []
+    for i, (N, K) in enumerate(shapes):
+        lin, x = workloads.integer_exact_case(N, K, M, 58, i)
+        y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+        cases.append((lin, x)); entries.append((pack(ptq, lin), dev(x), y, N, K))
+    plan = ptq.ptqtp_gemv_batch_plan(entries)
+    for fold in (0, 1):
+        try:
+            ptq.ptqtp_tune("small_fold", fold)
+            for ent in entries:
+                ent[2].fill_(float("nan"))
+            ptq.ptqtp_gemm_batch(plan, M)
+        finally:
+            ptq.ptqtp_tune("small_fold", -1)
+        for (lin, x), ent in zip(cases, entries):
+            y_ref, _ = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+            assert np.array_equal(ent[2].cpu().numpy().astype(np.float64), y_ref), f"fold={fold}"
 
 
 def test_gemv_zero_bound_gives_exact_zero(ptq):
