@@ -21,6 +21,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ptqtp_oracle.c")
 _SRC_Q = os.path.join(_HERE, "ptqtp_quantizer_oracle.c")
+_SRC_B = os.path.join(_HERE, "ptqtp_block_oracle.c")
 _LIB = os.path.join(_HERE, "libptqtp_oracle.so")
 _lib = None
 
@@ -35,11 +36,11 @@ class OracleError(ValueError):
 
 def build(force: bool = False) -> str:
     """Compile ptqtp_oracle.c with gcc (-O2, OpenMP for the row loop)."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_Q))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_Q), os.path.getmtime(_SRC_B))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-                               "-ffp-contract=off", "-o", tmp, _SRC, _SRC_Q, "-lm"])
+                               "-ffp-contract=off", "-o", tmp, _SRC, _SRC_Q, _SRC_B, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -65,6 +66,14 @@ def _load():
         lib.ptqtp_oracle_quantize.argtypes = [p, i64, i64, i64, i32, ctypes.c_double, p, p, p, p, p, p, p, p]
         lib.ptqtp_oracle_double_to_half_bits.restype = ctypes.c_uint16
         lib.ptqtp_oracle_double_to_half_bits.argtypes = [ctypes.c_double]
+        lib.ptqtp_oracle_silu.restype = ctypes.c_double
+        lib.ptqtp_oracle_silu.argtypes = [ctypes.c_double]
+        lib.ptqtp_oracle_swiglu.restype = i32
+        lib.ptqtp_oracle_swiglu.argtypes = [p, i64, i64, p]
+        lib.ptqtp_oracle_residual_add.restype = i32
+        lib.ptqtp_oracle_residual_add.argtypes = [p, p, i64, p]
+        lib.ptqtp_oracle_round_half.restype = ctypes.c_double
+        lib.ptqtp_oracle_round_half.argtypes = [ctypes.c_double]
         _lib = lib
     return _lib
 
@@ -190,3 +199,71 @@ def quantize(W, group: int = 128, max_iters: int = 50, eps: float = 1e-4) -> dic
         raise OracleError(rc)
     out["iters"] = iters.value
     return out
+
+
+# ---------------------------------------------------------------- decoder-block steps around the linears
+SILU_LIPSCHITZ = 1.1      # sup |silu'(z)| = 1.0998...
+
+
+def silu(z: float) -> float:
+    return _load().ptqtp_oracle_silu(float(z))
+
+
+def swiglu(y, I: int) -> np.ndarray:
+    """h[m,i] = silu(y[m,i]) * y[m,I+i] for y float64 [M, 2I] (gate rows first, then up rows)."""
+    y, py = _c(y, np.float64)
+    M = y.shape[0]
+    if y.ndim != 2 or y.shape[1] != 2 * I:
+        raise OracleError(ERR_SHAPE)
+    h = np.empty((M, I), dtype=np.float64)
+    rc = _load().ptqtp_oracle_swiglu(py, M, I, h.ctypes.data_as(ctypes.c_void_p))
+    if rc != OK:
+        raise OracleError(rc)
+    return h
+
+
+def residual_add(y, r16) -> np.ndarray:
+    """y + r with r float16 (widened exactly), float64 result of y's shape."""
+    y, py = _c(y, np.float64)
+    r16 = np.ascontiguousarray(r16)
+    if r16.dtype != np.float16 or r16.shape != y.shape:
+        raise OracleError(ERR_SHAPE)
+    out = np.empty_like(y)
+    rc = _load().ptqtp_oracle_residual_add(py, r16.view(np.uint16).ctypes.data_as(ctypes.c_void_p), y.size,
+                                           out.ctypes.data_as(ctypes.c_void_p))
+    if rc != OK:
+        raise OracleError(rc)
+    return out
+
+
+def round_half(v) -> np.ndarray:
+    """Each float64 rounded once to the nearest binary16 (ties to even), returned as float64."""
+    lib = _load()
+    v = np.asarray(v, dtype=np.float64)
+    return np.array([lib.ptqtp_oracle_round_half(float(t)) for t in v.ravel()], dtype=np.float64).reshape(v.shape)
+
+
+def stage(lin: dict, x, epilogue: str = "none", residual=None, threads: int = 1) -> dict:
+    """One stage of a decode chain in float64: the linear, then the epilogue.
+
+    epilogue "none":   out = y (+ residual)
+             "swiglu": lin stacks gate rows over up rows (N = 2I); out = silu(gate) * up (+ residual)
+    Returns {"out": exact float64 value, "err": E} where E[m,n] bounds the change of `out` when every
+    entry of the linear's result moves by at most its L1 bound B (first order: for swiglu
+    E = 1.1 * B_gate * |up| + |silu(gate)| * B_up).  A result with relative error tau in the
+    linear is off by at most tau * E (+ tau^2 * 1.1 * B_gate * B_up for swiglu)."""
+    y, B = forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, group=lin.get("group", 128), threads=threads)
+    if epilogue == "none":
+        out, err, err2 = y, B, np.zeros_like(B)
+    elif epilogue == "swiglu":
+        I = y.shape[1] // 2
+        out = swiglu(y, I)
+        g, u = y[:, :I], y[:, I:]
+        sg = np.array([silu(t) for t in g.ravel()]).reshape(g.shape)
+        err = SILU_LIPSCHITZ * B[:, :I] * np.abs(u) + np.abs(sg) * B[:, I:]
+        err2 = SILU_LIPSCHITZ * B[:, :I] * B[:, I:]
+    else:
+        raise ValueError(epilogue)
+    if residual is not None:
+        out = residual_add(out, residual)
+    return {"out": out, "err": err, "err2": err2}
