@@ -55,6 +55,14 @@ def _load():
         lib.ptqtp_gemm_small.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
         lib.ptqtp_gemm.restype = i32
         lib.ptqtp_gemm.argtypes = [p, p, p, i32, i64, i64, i64, i32, p, sz, p]
+        lib.ptqtp_chain_plan_bytes.restype = sz
+        lib.ptqtp_chain_plan_bytes.argtypes = [p, i32, i32]
+        lib.ptqtp_chain_plan.restype = i32
+        lib.ptqtp_chain_plan.argtypes = [p, i32, i32, p, sz, p]
+        lib.ptqtp_chain_run.restype = i32
+        lib.ptqtp_chain_run.argtypes = [p, i32, i32, p, i32, p]
+        lib.ptqtp_chain_status.restype = i32
+        lib.ptqtp_chain_status.argtypes = [p, p, p]
         lib.ptqtp_batch_plan_bytes.restype = sz
         lib.ptqtp_batch_plan_bytes.argtypes = [p, i32, i32]
         lib.ptqtp_batch_items.restype = i64
@@ -240,3 +248,62 @@ def ptqtp_quantize(W: torch.Tensor, group: int = 128, max_iters: int = 50, eps: 
     if st:
         raise PtqtpError(st, "ptqtp_quantize")
     return T1, T2, a1, a2, iters
+
+
+PTQTP_EPI_NONE, PTQTP_EPI_SWIGLU = 0, 1
+PTQTP_CHAIN_LAUNCHES, PTQTP_CHAIN_PERSISTENT = 0, 1
+
+
+class _Stage(ctypes.Structure):
+    _fields_ = [("packed", ctypes.c_void_p), ("x", ctypes.c_void_p), ("y", ctypes.c_void_p), ("residual", ctypes.c_void_p),
+                ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("epilogue", ctypes.c_int32), ("y_dtype", ctypes.c_int32),
+                ("level", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class ChainPlan:
+    """Device-side table for ptqtp_chain_run; keeps the host stage array and the tensors it names alive."""
+
+    def __init__(self, plan: torch.Tensor, arr, count: int, group: int, keep):
+        self.plan, self.arr, self.count, self.group, self._keep = plan, arr, count, group, keep
+
+
+def ptqtp_chain_plan(stages, group: int = 128) -> ChainPlan:
+    """stages: sequence of dicts with packed, x, y, N, K and optionally residual (tensor or None),
+    epilogue (PTQTP_EPI_*), level (int); y's torch dtype (float32 / float16) gives y_dtype."""
+    n = len(stages)
+    arr = (_Stage * max(n, 1))()
+    keep = []
+    for i, s in enumerate(stages):
+        y = s["y"]
+        if y.dtype not in (torch.float32, torch.float16):
+            raise PtqtpError(5, "ptqtp_chain_plan")
+        res = s.get("residual")
+        arr[i] = _Stage(_dev(s["packed"], torch.uint8, "packed"), _dev(s["x"], torch.float16, "x"), _dev(y, y.dtype, "y"),
+                        _dev(res, torch.float16, "residual") if res is not None else None,
+                        int(s["N"]), int(s["K"]), int(s.get("epilogue", PTQTP_EPI_NONE)),
+                        PTQTP_F32 if y.dtype == torch.float32 else PTQTP_F16, int(s.get("level", i)), 0)
+        keep += [s["packed"], s["x"], y, res]
+    lib = _load()
+    nbytes = int(lib.ptqtp_chain_plan_bytes(arr, n, group))
+    if nbytes == 0:
+        raise PtqtpError(2, "ptqtp_chain_plan_bytes")
+    plan = torch.empty(nbytes, dtype=torch.uint8, device=stages[0]["packed"].device)
+    st = lib.ptqtp_chain_plan(arr, n, group, plan.data_ptr(), nbytes, _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_chain_plan")
+    return ChainPlan(plan, arr, n, group, keep)
+
+
+def ptqtp_chain_run(plan: ChainPlan, mode: int = PTQTP_CHAIN_LAUNCHES) -> None:
+    st = _load().ptqtp_chain_run(plan.arr, plan.count, plan.group, plan.plan.data_ptr(), int(mode), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_chain_run")
+
+
+def ptqtp_chain_status(plan: ChainPlan) -> int:
+    """Status word of the last persistent run (synchronises the current stream)."""
+    out = ctypes.c_int32(-1)
+    st = _load().ptqtp_chain_status(plan.plan.data_ptr(), ctypes.byref(out), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_chain_status")
+    return int(out.value)

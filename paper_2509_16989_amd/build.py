@@ -6,7 +6,7 @@ import subprocess
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SOURCES = [os.path.join(PKG, "csrc", "ptqtp.hip"), os.path.join(PKG, "csrc", "ptqtp_quantize.hip")]
+SOURCES = [os.path.join(PKG, "csrc", n) for n in ("ptqtp.hip", "ptqtp_quantize.hip", "ptqtp_chain.hip")]
 LIB = os.path.join(PKG, "libptqtp.so")
 
 HIPCC_FLAGS = [

@@ -30,7 +30,8 @@ def test_header_symbols_exported(lib):
     assert {"ptqtp_pack", "ptqtp_unpack", "ptqtp_gemv", "ptqtp_gemm_small", "ptqtp_packed_bytes",
             "ptqtp_workspace_bytes", "ptqtp_status_string", "ptqtp_version", "ptqtp_tune", "ptqtp_gemm",
             "ptqtp_gemv_batch", "ptqtp_gemv_batch_plan", "ptqtp_batch_items", "ptqtp_batch_plan_bytes",
-            "ptqtp_quantize", "ptqtp_quantize_workspace_bytes"} <= set(names)
+            "ptqtp_quantize", "ptqtp_quantize_workspace_bytes", "ptqtp_gemm_batch", "ptqtp_chain_plan_bytes",
+            "ptqtp_chain_plan", "ptqtp_chain_run", "ptqtp_chain_status"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in ptqtp.h but not exported"
 
@@ -77,6 +78,48 @@ def test_batch_plan_validation(lib):
     assert lib.ptqtp_gemv_batch_plan(arr, 3, 0, 128, fake, 1 << 20, None) == 6
     assert lib.ptqtp_gemv_batch(None, 5, None) == 1
     assert lib.ptqtp_gemv_batch(fake, 0, None) == 2
+
+
+def test_chain_plan_validation(lib):
+    from paper_2509_16989_amd.binding import _Stage
+    def stages():
+        arr = (_Stage * 3)()
+        arr[0] = _Stage(0x10000, 0x20000, 0x30000, None, 4096, 4096, 0, 1, 0, 0)
+        arr[1] = _Stage(0x10000, 0x30000, 0x40000, 0x20000, 960, 4096, 1, 1, 1, 0)      # gated pair: 960/32 = 30 items
+        arr[2] = _Stage(0x10000, 0x40000, 0x50000, None, 100, 512 - 128, 0, 0, 5, 0)     # levels need not be dense
+        return arr
+    arr = stages()
+    items = 256 + 30 + 7
+    want = 256 + 64 * 4 + 3 * 72 + 4 * items
+    assert lib.ptqtp_chain_plan_bytes(arr, 3, 128) == (want + 255) // 256 * 256
+    assert lib.ptqtp_chain_plan_bytes(arr, 0, 128) == 0
+    assert lib.ptqtp_chain_plan_bytes(arr, 3, 64) == 0
+    assert lib.ptqtp_chain_plan_bytes(None, 3, 128) == 0
+    fake = ctypes.c_void_p(0x100000)
+    assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 16, None) == 4
+    assert lib.ptqtp_chain_plan(arr, 3, 128, None, 1 << 20, None) == 1
+    assert lib.ptqtp_chain_plan(arr, 3, 128, ctypes.c_void_p(0x100010), 1 << 20, None) == 6
+    arr = stages(); arr[1].N = 944          # gated stage: N must be a multiple of 32
+    assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 1 << 20, None) == 2
+    arr = stages(); arr[2].level = 0        # levels must not decrease
+    assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 1 << 20, None) == 2
+    arr = stages(); arr[0].epilogue = 7
+    assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 1 << 20, None) == 2
+    arr = stages(); arr[0].y_dtype = 3
+    assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 1 << 20, None) == 5
+    arr = stages(); arr[1].K = 4000
+    assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 1 << 20, None) == 2
+    arr = stages(); arr[2].y = 0
+    assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 1 << 20, None) == 1
+    arr = stages(); arr[1].residual = 0x20002
+    assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 1 << 20, None) == 6
+    arr = stages()
+    assert lib.ptqtp_chain_run(arr, 3, 128, None, 0, None) == 1
+    assert lib.ptqtp_chain_run(arr, 3, 128, fake, 2, None) == 2
+    assert lib.ptqtp_chain_status(None, None, None) == 1
+    assert lib.ptqtp_tune(b"chain_spin_limit", -1) == 2
+    assert lib.ptqtp_tune(b"chain_sync", 2) == 2
+    assert lib.ptqtp_tune(b"chain_sync", -1) == 0
 
 
 def test_quantize_validation(lib):

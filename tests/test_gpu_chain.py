@@ -1,0 +1,186 @@
+"""GPU parity for the decode chain: fused epilogues (gated-MLP product, residual add, fp16
+activations) and dependent stages, per-level launches and the persistent launch, against the
+fp64 oracle stage by stage.
+
+A stage is checked against the oracle evaluated on the input the GPU actually gave it (the
+previous stage's fp16 output, read back), so each comparison isolates one stage.  Bars: with E
+the oracle's first-order bound for the stage (the linear's L1 bound B pushed through the
+epilogue), |out_gpu - out_oracle| <= 2e-3 * E + second-order term (+ 2^-11 |out| for an fp16
+store), and a regression gate of 1e-5 * E in place of 2e-3 * E.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL, TIGHT = 2e-3, 1e-5
+HALF_ULP = 2.0 ** -11 * 1.001
+
+
+@pytest.fixture(scope="module")
+def ptq():
+    import paper_2509_16989_amd as p
+    return p
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def pack(ptq, lin):
+    return ptq.ptqtp_pack(dev(lin["T1"]), dev(lin["T2"]), dev(lin["a1"]), dev(lin["a2"]))
+
+
+def check_stage(out_gpu, lin, x16, epilogue, residual16):
+    """out_gpu: tensor [n_out]; x16 / residual16: numpy float16 as the GPU saw them."""
+    st = oracle.stage(lin, x16[None, :], epilogue, residual=None if residual16 is None else residual16[None, :], threads=8)
+    ref, E, E2 = st["out"][0], st["err"][0], st["err2"][0]
+    got = out_gpu.detach().cpu().numpy().astype(np.float64)
+    assert got.shape == ref.shape and np.all(np.isfinite(got))
+    rounding = HALF_ULP * np.abs(ref) + 1e-7 if out_gpu.dtype == torch.float16 else 2.0 ** -23 * np.abs(ref)
+    err = np.abs(got - ref)
+    assert np.all(err <= TOL * E + TOL * TOL * E2 + rounding), f"bar: {(err / np.maximum(E, 1e-300)).max():.3e}"
+    assert np.all(err <= TIGHT * E + rounding), f"regression gate: {((err - rounding) / np.maximum(E, 1e-300)).max():.3e}"
+
+
+MODES = [("launches", 0, -1), ("persistent_fences", 1, 0), ("persistent_coherent", 1, 1)]
+
+
+def run_chain(ptq, plan, mode, sync):
+    try:
+        ptq.ptqtp_tune("chain_sync", sync)
+        ptq.ptqtp_chain_run(plan, mode)
+    finally:
+        ptq.ptqtp_tune("chain_sync", -1)
+    if mode == ptq.PTQTP_CHAIN_PERSISTENT:
+        assert ptq.ptqtp_chain_status(plan) == 0
+    else:
+        torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name,mode,sync", MODES)
+@pytest.mark.parametrize("N,K,epi,res,ydt", [
+    (200, 640, "none", False, torch.float32), (200, 640, "none", True, torch.float16), (1024, 1024, "none", True, torch.float32),
+    (64, 128, "swiglu", False, torch.float16), (960, 384, "swiglu", False, torch.float32), (2048, 1024, "swiglu", True, torch.float16),
+    (33, 4096, "none", False, torch.float16),
+])
+def test_chain_single_stage(ptq, name, mode, sync, N, K, epi, res, ydt):
+    lin = workloads.make_linear(N, K, 80, N, K)
+    x = workloads.make_x(1, K, 80, N)[0]
+    n_out = N // 2 if epi == "swiglu" else N
+    r = workloads.make_x(1, n_out, 80, N, 7)[0] if res else None
+    y = torch.full((n_out,), float("nan"), dtype=ydt, device="cuda:0")
+    plan = ptq.ptqtp_chain_plan([dict(packed=pack(ptq, lin), x=dev(x), y=y, N=N, K=K, level=0,
+                                      residual=dev(r) if res else None,
+                                      epilogue=ptq.PTQTP_EPI_SWIGLU if epi == "swiglu" else ptq.PTQTP_EPI_NONE)])
+    run_chain(ptq, plan, mode, sync)
+    check_stage(y, lin, x, epi, r)
+
+
+def build_stack(ptq, layers, H, KV, I, seed):
+    """layers x {qkv -> o (+residual) -> gate_up (gated product) -> down (+residual)}; the attention
+    between qkv and o is not part of the path: o reads the first H entries of qkv's output."""
+    lins, stages, bufs = [], [], {}
+    bufs["x0"] = torch.zeros(H, dtype=torch.float16, device="cuda:0")
+    cur = bufs["x0"]
+    level = 0
+    for l in range(layers):
+        qkv = workloads.make_linear(H + 2 * KV, H, seed, l, 1)
+        o = workloads.make_linear(H, H, seed, l, 2)
+        gu = workloads.make_linear(2 * I, H, seed, l, 3)
+        dn = workloads.make_linear(H, I, seed, l, 4)
+        t_qkv = torch.zeros(H + 2 * KV, dtype=torch.float16, device="cuda:0")
+        t_attn = torch.zeros(H, dtype=torch.float16, device="cuda:0")
+        t_h = torch.zeros(I, dtype=torch.float16, device="cuda:0")
+        t_out = torch.zeros(H, dtype=torch.float16, device="cuda:0")
+        specs = [(qkv, cur, t_qkv, None, "none"), (o, t_qkv, t_attn, cur, "none"),
+                 (gu, t_attn, t_h, None, "swiglu"), (dn, t_h, t_out, t_attn, "none")]
+        for lin, xin, yout, res, epi in specs:
+            stages.append(dict(packed=pack(ptq, lin), x=xin, y=yout, N=lin["N"], K=lin["K"], level=level, residual=res,
+                               epilogue=ptq.PTQTP_EPI_SWIGLU if epi == "swiglu" else ptq.PTQTP_EPI_NONE))
+            lins.append((lin, xin, yout, res, epi))
+            level += 1
+        cur = t_out
+    return lins, stages, bufs
+
+
+@pytest.mark.parametrize("name,mode,sync", MODES)
+def test_chain_dependent_stack(ptq, name, mode, sync):
+    H, KV, I, layers = 384, 128, 640, 3
+    lins, stages, bufs = build_stack(ptq, layers, H, KV, I, 81)
+    plan = ptq.ptqtp_chain_plan(stages)
+    # several runs with different inputs: a stage that read a stale copy of its input would show
+    for rep in range(3):
+        x0 = workloads.make_x(1, H, 81, 100 + rep)[0]
+        bufs["x0"].copy_(dev(x0))
+        run_chain(ptq, plan, mode, sync)
+        for lin, xin, yout, res, epi in lins:
+            k = lin["K"]
+            x16 = xin.cpu().numpy()[:k]
+            r16 = None if res is None else res.cpu().numpy()
+            check_stage(yout, lin, x16, epi, r16)
+        # the last layer's output is not the residual passed through: the chain did something
+        assert not torch.equal(lins[-1][2], lins[-1][3])
+
+
+def test_chain_modes_agree_bitwise(ptq):
+    # same kernel arithmetic in every mode: identical bits
+    H, KV, I, layers = 256, 128, 384, 2
+    lins, stages, bufs = build_stack(ptq, layers, H, KV, I, 82)
+    plan = ptq.ptqtp_chain_plan(stages)
+    bufs["x0"].copy_(dev(workloads.make_x(1, H, 82, 5)[0]))
+    outs = []
+    for name, mode, sync in MODES:
+        for lin, xin, yout, res, epi in lins:
+            yout.zero_()
+        run_chain(ptq, plan, mode, sync)
+        outs.append([t[2].clone() for t in lins])
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
+
+
+def test_chain_independent_stages_share_a_level(ptq):
+    # q, k, v as three stages of one level, then o on the next
+    H = 256
+    x = workloads.make_x(1, H, 83, 1)[0]
+    xd = dev(x)
+    parts = [workloads.make_linear(n, H, 83, i) for i, n in enumerate((256, 64, 48))]
+    outs = [torch.zeros(p["N"], dtype=torch.float16, device="cuda:0") for p in parts]
+    o = workloads.make_linear(H, H, 83, 9)
+    yo = torch.zeros(H, dtype=torch.float32, device="cuda:0")
+    stages = [dict(packed=pack(ptq, p), x=xd, y=y, N=p["N"], K=H, level=0) for p, y in zip(parts, outs)]
+    stages.append(dict(packed=pack(ptq, o), x=outs[0], y=yo, N=H, K=H, level=1, residual=xd))
+    plan = ptq.ptqtp_chain_plan(stages)
+    for name, mode, sync in MODES:
+        run_chain(ptq, plan, mode, sync)
+        for p, y in zip(parts, outs):
+            check_stage(y, p, x, "none", None)
+        check_stage(yo, o, outs[0].cpu().numpy(), "none", x)
+
+
+def test_chain_bounded_wait_times_out_cleanly(ptq):
+    # with one poll allowed, the second level gives up at once: the kernel still ends normally and says so
+    big = workloads.make_linear(4096, 4096, 84, 1)
+    small = workloads.make_linear(64, 4096, 84, 2)
+    x = dev(workloads.make_x(1, 4096, 84, 3)[0])
+    mid = torch.zeros(4096, dtype=torch.float16, device="cuda:0")
+    out = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    stages = [dict(packed=pack(ptq, big), x=x, y=mid, N=4096, K=4096, level=0),
+              dict(packed=pack(ptq, small), x=mid, y=out, N=64, K=4096, level=1)]
+    plan = ptq.ptqtp_chain_plan(stages)
+    try:
+        ptq.ptqtp_tune("chain_spin_limit", 1)
+        ptq.ptqtp_chain_run(plan, ptq.PTQTP_CHAIN_PERSISTENT)
+        assert ptq.ptqtp_chain_status(plan) == 8          # PTQTP_ERR_WAIT
+    finally:
+        ptq.ptqtp_tune("chain_spin_limit", 0)
+    # the same plan runs correctly afterwards
+    ptq.ptqtp_chain_run(plan, ptq.PTQTP_CHAIN_PERSISTENT)
+    assert ptq.ptqtp_chain_status(plan) == 0
+    check_stage(mid, big, x.cpu().numpy(), "none", None)
+    check_stage(out, small, mid.cpu().numpy(), "none", None)
