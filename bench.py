@@ -294,6 +294,10 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
             nbytes = sum(algorithmic_bytes(n, k, M) for n, k in dims)
             res["stack_batched"][f"M{M}"] = {"us_per_step": round(ms * 1e3, 1), "GBps": round(nbytes / ms / 1e6, 1)}
             del xm, ym, plan
+        # config 3 with the activations really depending on each other: per layer qkv -> o (+residual) ->
+        # gate|up (silu(gate)*up) -> down (+residual), fp16 activations, one launch per stage (128 launches)
+        # replayed from a hipGraph.  Attention itself is not part of the path: o reads the q part of qkv's output.
+        res["dependent_chain"] = dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream)
         # the step before the path: PTQTP decomposition of Gaussian fp16 weights (paper settings: T_max 50, eps 1e-4)
         res["quantize"] = {}
         for name in ("q", "gate"):
@@ -318,6 +322,56 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
         res["quantize"]["cpu_oracle_256x4096"] = {"ms": round(dt * 1e3, 1), "iters": q["iters"], "cores": 1,
                                                   "ns_per_weight_iter": round(dt * 1e9 / (256 * 4096 * q["iters"]), 2)}
     return res
+
+
+def dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream):
+    """Fuse the stack's q|k|v and gate|up blobs on the device (unpack, stack the rows, pack), build the
+    decode chain over all layers and time one step.  The scales of o and down are multiplied by 1/8 and 1/32
+    (exact in fp16) so that the residual stream of 32 random layers stays finite."""
+    dev = blobs[0].device
+    by = {(layer, name): i for i, (layer, name) in enumerate(jobs)}
+    layers = 1 + max(layer for layer, _ in jobs)
+
+    def parts(layer, names, scale=None):
+        T1, T2, a1, a2 = [], [], [], []
+        for nm in names:
+            i = by[(layer, nm)]
+            t1, t2, s1, s2 = ptq.ptqtp_unpack(blobs[i], dims[i][0], dims[i][1])
+            T1.append(t1); T2.append(t2); a1.append(s1); a2.append(s2)
+        cat = [torch.cat(v) for v in (T1, T2, a1, a2)]
+        if scale is not None:
+            cat[2] = cat[2] * scale
+            cat[3] = cat[3] * scale
+        return ptq.ptqtp_pack(*cat, check=False), cat[0].shape[0], cat[0].shape[1]
+
+    H = dims[by[(0, "q")]][1]
+    x0 = torch.randn(H, device=dev).half()
+    stages, cur, level, nbytes = [], x0, 0, 0
+    for layer in range(layers):
+        fused = {"qkv": parts(layer, ("q", "k", "v")), "o": parts(layer, ("o",), 0.125),
+                 "gu": parts(layer, ("gate", "up")), "dn": parts(layer, ("down",), 0.03125)}
+        I = fused["gu"][1] // 2
+        t_qkv = torch.zeros(fused["qkv"][1], dtype=torch.float16, device=dev)
+        t_attn = torch.zeros(H, dtype=torch.float16, device=dev)
+        t_h = torch.zeros(I, dtype=torch.float16, device=dev)
+        t_out = torch.zeros(H, dtype=torch.float16, device=dev)
+        for key, xin, yout, resid, epi in (("qkv", cur, t_qkv, None, ptq.PTQTP_EPI_NONE), ("o", t_qkv, t_attn, cur, ptq.PTQTP_EPI_NONE),
+                                          ("gu", t_attn, t_h, None, ptq.PTQTP_EPI_SWIGLU), ("dn", t_h, t_out, t_attn, ptq.PTQTP_EPI_NONE)):
+            b, n, k = fused[key]
+            stages.append(dict(packed=b, x=xin, y=yout, N=n, K=k, level=level, residual=resid, epilogue=epi))
+            nbytes += algorithmic_bytes(n, k, 1)
+            level += 1
+        cur = t_out
+    plan = ptq.ptqtp_chain_plan(stages)
+    ptq.ptqtp_chain_run(plan)
+    stream.synchronize()
+    finite = bool(torch.isfinite(cur.float()).all())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        ptq.ptqtp_chain_run(plan)
+    ms = time_steps(torch, lambda: g.replay(), 100, 20, stream)
+    return {"us_per_step": round(ms * 1e3, 1), "GBps": round(nbytes / ms / 1e6, 1), "launches": len(stages),
+            "layers": layers, "output_finite": finite}
 
 
 def cpu_baseline(layer0, names):

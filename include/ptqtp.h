@@ -51,8 +51,7 @@ enum {
     PTQTP_ERR_SIZE   = 4,  /* packed_bytes / workspace_bytes smaller than required         */
     PTQTP_ERR_DTYPE  = 5,  /* y_dtype is neither PTQTP_F32 nor PTQTP_F16                   */
     PTQTP_ERR_ALIGN  = 6,  /* a device pointer is not aligned as required                  */
-    PTQTP_ERR_HIP    = 7,  /* the HIP runtime reported an error at launch                  */
-    PTQTP_ERR_WAIT   = 8   /* ptqtp_chain_status: a bounded device-side wait ran out       */
+    PTQTP_ERR_HIP    = 7   /* the HIP runtime reported an error at launch                  */
 };
 
 enum { PTQTP_F32 = 0, PTQTP_F16 = 1 };   /* y_dtype */
@@ -199,21 +198,12 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
  *
  *   ptqtp_chain_plan   writes the device-side table (one-time, stream-ordered): plan receives
  *                      ptqtp_chain_plan_bytes(...) bytes, 256-byte aligned
- *   ptqtp_chain_run    runs the chain.  mode PTQTP_CHAIN_LAUNCHES: one launch per level, in
- *                      stream order.  mode PTQTP_CHAIN_PERSISTENT: ONE launch for all levels;
- *                      workgroups take work items in level order from a device counter, start
- *                      streaming their packed rows at once, and wait (device-side completion
- *                      counter per level) only before they read activations, so the HBM stream
- *                      does not drain at level boundaries.  Every wait is bounded: if it runs
- *                      out, the kernel still finishes normally, results are invalid and
- *                      ptqtp_chain_status reports PTQTP_ERR_WAIT.  `stages`, `count` must be
- *                      the ones the plan was written from.  Runs of one plan must not overlap.
- *   ptqtp_chain_status copies the status word of the last run to *status_host
- *                      (PTQTP_OK or PTQTP_ERR_WAIT); SYNCHRONISES the stream.
+ *   ptqtp_chain_run    runs the chain: one launch per level, in stream order (capture it in a
+ *                      HIP graph to replay a decode step); a level with few work items gets more
+ *                      waves per item.  `stages`, `count` must be the ones the plan was written from.
  * ptqtp_chain_plan_bytes returns 0 for invalid arguments.
  */
 enum { PTQTP_EPI_NONE = 0, PTQTP_EPI_SWIGLU = 1 };
-enum { PTQTP_CHAIN_LAUNCHES = 0, PTQTP_CHAIN_PERSISTENT = 1 };
 #define PTQTP_CHAIN_MAX_STAGES 4096
 typedef struct ptqtp_stage {
     const void *packed;        /* device, blob from ptqtp_pack for this N, K */
@@ -231,8 +221,7 @@ size_t ptqtp_chain_plan_bytes(const ptqtp_stage *stages, int32_t count, int32_t 
 ptqtp_status ptqtp_chain_plan(const ptqtp_stage *stages, int32_t count, int32_t group,
                               void *plan, size_t plan_bytes, void *stream);
 ptqtp_status ptqtp_chain_run(const ptqtp_stage *stages, int32_t count, int32_t group,
-                             void *plan, int32_t mode, void *stream);
-ptqtp_status ptqtp_chain_status(const void *plan, int32_t *status_host, void *stream);
+                             const void *plan, void *stream);
 
 /*
  * The step before the path: PTQTP decomposition of an fp16 weight matrix into the two trit
@@ -270,10 +259,7 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
  * (1 = use the MFMA tile for every batch > 1, -1 = default), "tile_variant" (1 = always the
  * 256 x 128 tile, 2 = always the 128 x 128 two-waves-per-SIMD tile, 0 = default: by problem size), "small_rows" (row tiles per item of
  * the small-batch kernel, 1 or 2), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation
- * loads, -1/1 = shared activation tile), "chain_spin_limit" (polls a bounded wait of ptqtp_chain_run may take, >= 1; tests of the
- * time-out path set it to 1), "chain_sync" (PTQTP_CHAIN_PERSISTENT: 0 = agent-scope fences around the level
- * counters, 1 = write-through stores and coherent loads for activations and no cache-wide fence),
- * "small_fold" (ptqtp_gemm_batch with two row tiles per wave:
+ * loads, -1/1 = shared activation tile), "small_fold" (ptqtp_gemm_batch with two row tiles per wave:
  * 1 = multiply the group scales into the expanded trits before the matrix pipe, 0 = rescale the
  * per-group sums after it, -1 = default: before for more than 16 tokens);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an

@@ -60,9 +60,7 @@ def _load():
         lib.ptqtp_chain_plan.restype = i32
         lib.ptqtp_chain_plan.argtypes = [p, i32, i32, p, sz, p]
         lib.ptqtp_chain_run.restype = i32
-        lib.ptqtp_chain_run.argtypes = [p, i32, i32, p, i32, p]
-        lib.ptqtp_chain_status.restype = i32
-        lib.ptqtp_chain_status.argtypes = [p, p, p]
+        lib.ptqtp_chain_run.argtypes = [p, i32, i32, p, p]
         lib.ptqtp_batch_plan_bytes.restype = sz
         lib.ptqtp_batch_plan_bytes.argtypes = [p, i32, i32]
         lib.ptqtp_batch_items.restype = i64
@@ -251,7 +249,6 @@ def ptqtp_quantize(W: torch.Tensor, group: int = 128, max_iters: int = 50, eps: 
 
 
 PTQTP_EPI_NONE, PTQTP_EPI_SWIGLU = 0, 1
-PTQTP_CHAIN_LAUNCHES, PTQTP_CHAIN_PERSISTENT = 0, 1
 
 
 class _Stage(ctypes.Structure):
@@ -294,16 +291,8 @@ def ptqtp_chain_plan(stages, group: int = 128) -> ChainPlan:
     return ChainPlan(plan, arr, n, group, keep)
 
 
-def ptqtp_chain_run(plan: ChainPlan, mode: int = PTQTP_CHAIN_LAUNCHES) -> None:
-    st = _load().ptqtp_chain_run(plan.arr, plan.count, plan.group, plan.plan.data_ptr(), int(mode), _stream())
+def ptqtp_chain_run(plan: ChainPlan) -> None:
+    """One launch per level on the current stream."""
+    st = _load().ptqtp_chain_run(plan.arr, plan.count, plan.group, plan.plan.data_ptr(), _stream())
     if st:
         raise PtqtpError(st, "ptqtp_chain_run")
-
-
-def ptqtp_chain_status(plan: ChainPlan) -> int:
-    """Status word of the last persistent run (synchronises the current stream)."""
-    out = ctypes.c_int32(-1)
-    st = _load().ptqtp_chain_status(plan.plan.data_ptr(), ctypes.byref(out), _stream())
-    if st:
-        raise PtqtpError(st, "ptqtp_chain_status")
-    return int(out.value)

@@ -35,10 +35,6 @@
 #include "ptqtp.h"
 #include "ptqtp_device.hpp"
 
-namespace ptqtp_detail {
-extern int g_chain_spin_limit, g_chain_sync;   // ptqtp_chain.hip
-}
-
 namespace {
 
 struct BlobHeader {
@@ -1378,7 +1374,6 @@ const char *ptqtp_status_string(ptqtp_status s) {
         case PTQTP_ERR_DTYPE: return "unsupported output dtype";
         case PTQTP_ERR_ALIGN: return "misaligned pointer";
         case PTQTP_ERR_HIP: return "HIP runtime error";
-        case PTQTP_ERR_WAIT: return "a bounded device-side wait ran out";
         default: return "unknown status";
     }
 }
@@ -1555,16 +1550,6 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
 
 ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!key) return PTQTP_ERR_NULL;
-    if (!strcmp(key, "chain_spin_limit")) {
-        if (value < 0) return PTQTP_ERR_SHAPE;
-        ptqtp_detail::g_chain_spin_limit = value;
-        return PTQTP_OK;
-    }
-    if (!strcmp(key, "chain_sync")) {
-        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
-        ptqtp_detail::g_chain_sync = value;
-        return PTQTP_OK;
-    }
     if (!strcmp(key, "small_fold")) {
         if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
         g_tune_small_fold = value;

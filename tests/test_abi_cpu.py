@@ -31,7 +31,7 @@ def test_header_symbols_exported(lib):
             "ptqtp_workspace_bytes", "ptqtp_status_string", "ptqtp_version", "ptqtp_tune", "ptqtp_gemm",
             "ptqtp_gemv_batch", "ptqtp_gemv_batch_plan", "ptqtp_batch_items", "ptqtp_batch_plan_bytes",
             "ptqtp_quantize", "ptqtp_quantize_workspace_bytes", "ptqtp_gemm_batch", "ptqtp_chain_plan_bytes",
-            "ptqtp_chain_plan", "ptqtp_chain_run", "ptqtp_chain_status"} <= set(names)
+            "ptqtp_chain_plan", "ptqtp_chain_run"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in ptqtp.h but not exported"
 
@@ -90,7 +90,7 @@ def test_chain_plan_validation(lib):
         return arr
     arr = stages()
     items = 256 + 30 + 7
-    want = 256 + 64 * 4 + 3 * 72 + 4 * items
+    want = 256 + 3 * 72 + 4 * items      # header, table, item map
     assert lib.ptqtp_chain_plan_bytes(arr, 3, 128) == (want + 255) // 256 * 256
     assert lib.ptqtp_chain_plan_bytes(arr, 0, 128) == 0
     assert lib.ptqtp_chain_plan_bytes(arr, 3, 64) == 0
@@ -114,12 +114,10 @@ def test_chain_plan_validation(lib):
     arr = stages(); arr[1].residual = 0x20002
     assert lib.ptqtp_chain_plan(arr, 3, 128, fake, 1 << 20, None) == 6
     arr = stages()
-    assert lib.ptqtp_chain_run(arr, 3, 128, None, 0, None) == 1
-    assert lib.ptqtp_chain_run(arr, 3, 128, fake, 2, None) == 2
-    assert lib.ptqtp_chain_status(None, None, None) == 1
-    assert lib.ptqtp_tune(b"chain_spin_limit", -1) == 2
-    assert lib.ptqtp_tune(b"chain_sync", 2) == 2
-    assert lib.ptqtp_tune(b"chain_sync", -1) == 0
+    assert lib.ptqtp_chain_run(arr, 3, 128, None, None) == 1
+    assert lib.ptqtp_chain_run(arr, 3, 128, ctypes.c_void_p(0x100010), None) == 6
+    arr[1].N = 944
+    assert lib.ptqtp_chain_run(arr, 3, 128, fake, None) == 2
 
 
 def test_quantize_validation(lib):

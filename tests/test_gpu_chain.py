@@ -1,6 +1,5 @@
 """GPU parity for the decode chain: fused epilogues (gated-MLP product, residual add, fp16
-activations) and dependent stages, per-level launches and the persistent launch, against the
-fp64 oracle stage by stage.
+activations) and dependent stages, one launch per level, against the fp64 oracle stage by stage.
 
 A stage is checked against the oracle evaluated on the input the GPU actually gave it (the
 previous stage's fp16 output, read back), so each comparison isolates one stage.  Bars: with E
@@ -47,28 +46,17 @@ def check_stage(out_gpu, lin, x16, epilogue, residual16):
     assert np.all(err <= TIGHT * E + rounding), f"regression gate: {((err - rounding) / np.maximum(E, 1e-300)).max():.3e}"
 
 
-MODES = [("launches", 0, -1), ("persistent_fences", 1, 0), ("persistent_coherent", 1, 1)]
+def run_chain(ptq, plan):
+    ptq.ptqtp_chain_run(plan)
+    torch.cuda.synchronize()
 
 
-def run_chain(ptq, plan, mode, sync):
-    try:
-        ptq.ptqtp_tune("chain_sync", sync)
-        ptq.ptqtp_chain_run(plan, mode)
-    finally:
-        ptq.ptqtp_tune("chain_sync", -1)
-    if mode == ptq.PTQTP_CHAIN_PERSISTENT:
-        assert ptq.ptqtp_chain_status(plan) == 0
-    else:
-        torch.cuda.synchronize()
-
-
-@pytest.mark.parametrize("name,mode,sync", MODES)
 @pytest.mark.parametrize("N,K,epi,res,ydt", [
     (200, 640, "none", False, torch.float32), (200, 640, "none", True, torch.float16), (1024, 1024, "none", True, torch.float32),
     (64, 128, "swiglu", False, torch.float16), (960, 384, "swiglu", False, torch.float32), (2048, 1024, "swiglu", True, torch.float16),
     (33, 4096, "none", False, torch.float16),
 ])
-def test_chain_single_stage(ptq, name, mode, sync, N, K, epi, res, ydt):
+def test_chain_single_stage(ptq, N, K, epi, res, ydt):
     lin = workloads.make_linear(N, K, 80, N, K)
     x = workloads.make_x(1, K, 80, N)[0]
     n_out = N // 2 if epi == "swiglu" else N
@@ -77,7 +65,7 @@ def test_chain_single_stage(ptq, name, mode, sync, N, K, epi, res, ydt):
     plan = ptq.ptqtp_chain_plan([dict(packed=pack(ptq, lin), x=dev(x), y=y, N=N, K=K, level=0,
                                       residual=dev(r) if res else None,
                                       epilogue=ptq.PTQTP_EPI_SWIGLU if epi == "swiglu" else ptq.PTQTP_EPI_NONE)])
-    run_chain(ptq, plan, mode, sync)
+    run_chain(ptq, plan)
     check_stage(y, lin, x, epi, r)
 
 
@@ -108,8 +96,7 @@ def build_stack(ptq, layers, H, KV, I, seed):
     return lins, stages, bufs
 
 
-@pytest.mark.parametrize("name,mode,sync", MODES)
-def test_chain_dependent_stack(ptq, name, mode, sync):
+def test_chain_dependent_stack(ptq):
     H, KV, I, layers = 384, 128, 640, 3
     lins, stages, bufs = build_stack(ptq, layers, H, KV, I, 81)
     plan = ptq.ptqtp_chain_plan(stages)
@@ -117,7 +104,7 @@ def test_chain_dependent_stack(ptq, name, mode, sync):
     for rep in range(3):
         x0 = workloads.make_x(1, H, 81, 100 + rep)[0]
         bufs["x0"].copy_(dev(x0))
-        run_chain(ptq, plan, mode, sync)
+        run_chain(ptq, plan)
         for lin, xin, yout, res, epi in lins:
             k = lin["K"]
             x16 = xin.cpu().numpy()[:k]
@@ -127,21 +114,31 @@ def test_chain_dependent_stack(ptq, name, mode, sync):
         assert not torch.equal(lins[-1][2], lins[-1][3])
 
 
-def test_chain_modes_agree_bitwise(ptq):
-    # same kernel arithmetic in every mode: identical bits
+def test_chain_replays_from_a_graph(ptq):
+    # a decode step captured once and replayed with new inputs, eager work in between
     H, KV, I, layers = 256, 128, 384, 2
     lins, stages, bufs = build_stack(ptq, layers, H, KV, I, 82)
     plan = ptq.ptqtp_chain_plan(stages)
-    bufs["x0"].copy_(dev(workloads.make_x(1, H, 82, 5)[0]))
-    outs = []
-    for name, mode, sync in MODES:
-        for lin, xin, yout, res, epi in lins:
-            yout.zero_()
-        run_chain(ptq, plan, mode, sync)
-        outs.append([t[2].clone() for t in lins])
-    for other in outs[1:]:
-        for a, b in zip(outs[0], other):
-            assert torch.equal(a, b)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ptq.ptqtp_chain_run(plan)
+        stream.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            ptq.ptqtp_chain_run(plan)
+        for rep in range(3):
+            bufs["x0"].copy_(dev(workloads.make_x(1, H, 82, 5 + rep)[0]))
+            for lin, xin, yout, res, epi in lins:
+                yout.zero_()
+            g.replay()
+            stream.synchronize()
+            replayed = [t[2].clone() for t in lins]
+            ptq.ptqtp_chain_run(plan)
+            stream.synchronize()
+            for a, t in zip(replayed, lins):
+                assert torch.equal(a, t[2])
+            for lin, xin, yout, res, epi in lins:
+                check_stage(yout, lin, xin.cpu().numpy()[:lin["K"]], epi, None if res is None else res.cpu().numpy())
 
 
 def test_chain_independent_stages_share_a_level(ptq):
@@ -156,31 +153,7 @@ def test_chain_independent_stages_share_a_level(ptq):
     stages = [dict(packed=pack(ptq, p), x=xd, y=y, N=p["N"], K=H, level=0) for p, y in zip(parts, outs)]
     stages.append(dict(packed=pack(ptq, o), x=outs[0], y=yo, N=H, K=H, level=1, residual=xd))
     plan = ptq.ptqtp_chain_plan(stages)
-    for name, mode, sync in MODES:
-        run_chain(ptq, plan, mode, sync)
-        for p, y in zip(parts, outs):
-            check_stage(y, p, x, "none", None)
-        check_stage(yo, o, outs[0].cpu().numpy(), "none", x)
-
-
-def test_chain_bounded_wait_times_out_cleanly(ptq):
-    # with one poll allowed, the second level gives up at once: the kernel still ends normally and says so
-    big = workloads.make_linear(4096, 4096, 84, 1)
-    small = workloads.make_linear(64, 4096, 84, 2)
-    x = dev(workloads.make_x(1, 4096, 84, 3)[0])
-    mid = torch.zeros(4096, dtype=torch.float16, device="cuda:0")
-    out = torch.zeros(64, dtype=torch.float32, device="cuda:0")
-    stages = [dict(packed=pack(ptq, big), x=x, y=mid, N=4096, K=4096, level=0),
-              dict(packed=pack(ptq, small), x=mid, y=out, N=64, K=4096, level=1)]
-    plan = ptq.ptqtp_chain_plan(stages)
-    try:
-        ptq.ptqtp_tune("chain_spin_limit", 1)
-        ptq.ptqtp_chain_run(plan, ptq.PTQTP_CHAIN_PERSISTENT)
-        assert ptq.ptqtp_chain_status(plan) == 8          # PTQTP_ERR_WAIT
-    finally:
-        ptq.ptqtp_tune("chain_spin_limit", 0)
-    # the same plan runs correctly afterwards
-    ptq.ptqtp_chain_run(plan, ptq.PTQTP_CHAIN_PERSISTENT)
-    assert ptq.ptqtp_chain_status(plan) == 0
-    check_stage(mid, big, x.cpu().numpy(), "none", None)
-    check_stage(out, small, mid.cpu().numpy(), "none", None)
+    run_chain(ptq, plan)
+    for p, y in zip(parts, outs):
+        check_stage(y, p, x, "none", None)
+    check_stage(yo, o, outs[0].cpu().numpy(), "none", x)
