@@ -133,6 +133,15 @@ ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, in
  * layer is a dense contraction -- an MFMA tile that stages activations in LDS and feeds
  * alpha*T (exact in fp16) to the matrix pipe.  Arguments as in ptqtp_gemm_small.
  */
+/*
+ * PTQTP_FUSED_PLANES, OR-ed into y_dtype of ptqtp_gemm only: from 256 tokens on, rebuild the weight
+ * before the matrix pipe, w16 = fp16(alpha1*t1 + alpha2*t2) -- ONE rounding per weight, both
+ * products being exact in fp16 -- and run one MFMA pass over w16 instead of one per plane (the
+ * "dequantization" forward Sec. "Inference Efficiency" names beside the dequantization-free one).
+ * The result is the exact layer of the rounded weights: |y - y_unfused| <= 2^-11 * B with B the
+ * L1 bound sum_k (|alpha1 t1| + |alpha2 t2|) |x_k|.  Below 256 tokens the flag has no effect.
+ */
+#define PTQTP_FUSED_PLANES 16
 #define PTQTP_GEMM_MAX_M 65536
 ptqtp_status ptqtp_gemm(const void *packed, const uint16_t *x, void *y, int32_t y_dtype,
                         int64_t M, int64_t N, int64_t K, int32_t group,

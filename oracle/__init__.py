@@ -74,6 +74,8 @@ def _load():
         lib.ptqtp_oracle_residual_add.argtypes = [p, p, i64, p]
         lib.ptqtp_oracle_round_half.restype = ctypes.c_double
         lib.ptqtp_oracle_round_half.argtypes = [ctypes.c_double]
+        lib.ptqtp_oracle_round_half_array.restype = None
+        lib.ptqtp_oracle_round_half_array.argtypes = [p, i64, p]
         _lib = lib
     return _lib
 
@@ -145,6 +147,18 @@ def forward_dense(T1, T2, a1, a2, x, group: int = 128) -> np.ndarray:
     if x.ndim == 1:
         x = x[None, :]
     return x @ W.T
+
+
+def forward_fused(T1, T2, a1, a2, x, group: int = 128):
+    """The "dequantization" forward with the weight held in binary16 (Sec. "Inference Efficiency"
+    names a dequantization forward beside the dequantization-free one): W16 = each entry of
+    W^ = alpha1 T1 + alpha2 T2 rounded ONCE to binary16, then y = x W16^T in float64.
+    Returns (y, B16) with B16 = |x| |W16|^T, both float64 [M, N]."""
+    W16 = round_half(reconstruct_dense(T1, T2, a1, a2, group))
+    x = np.asarray(x, dtype=np.float64)
+    if x.ndim == 1:
+        x = x[None, :]
+    return x @ W16.T, np.abs(x) @ np.abs(W16).T
 
 
 def pack_canonical(T) -> np.ndarray:
@@ -238,9 +252,10 @@ def residual_add(y, r16) -> np.ndarray:
 
 def round_half(v) -> np.ndarray:
     """Each float64 rounded once to the nearest binary16 (ties to even), returned as float64."""
-    lib = _load()
-    v = np.asarray(v, dtype=np.float64)
-    return np.array([lib.ptqtp_oracle_round_half(float(t)) for t in v.ravel()], dtype=np.float64).reshape(v.shape)
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    out = np.empty_like(v)
+    _load().ptqtp_oracle_round_half_array(v.ctypes.data_as(ctypes.c_void_p), v.size, out.ctypes.data_as(ctypes.c_void_p))
+    return out
 
 
 def stage(lin: dict, x, epilogue: str = "none", residual=None, threads: int = 1) -> dict:

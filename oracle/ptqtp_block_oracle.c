@@ -73,3 +73,8 @@ double ptqtp_oracle_round_half(double v)
     if (q >= 65520.0) q = INFINITY;
     return v < 0 ? -q : q;
 }
+
+void ptqtp_oracle_round_half_array(const double *v, int64_t count, double *out)
+{
+    for (int64_t i = 0; i < count; ++i) out[i] = ptqtp_oracle_round_half(v[i]);
+}

@@ -11,6 +11,7 @@ import os
 import torch
 
 PTQTP_F32, PTQTP_F16 = 0, 1
+PTQTP_FUSED_PLANES = 16      # OR into ptqtp_gemm's y_dtype
 PTQTP_GEMM_SMALL_MAX_M = 64
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -150,7 +151,7 @@ def ptqtp_unpack(packed: torch.Tensor, N: int, K: int, M: int = 1, group: int = 
 
 
 def _forward(fn, where, packed, x, N, K, M, group, y_dtype, out):
-    ydt = torch.float32 if y_dtype == PTQTP_F32 else torch.float16
+    ydt = torch.float32 if (y_dtype & ~PTQTP_FUSED_PLANES) == PTQTP_F32 else torch.float16
     if out is None:
         out = torch.empty((M, N), dtype=ydt, device=x.device)
     st = fn(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"), _dev(out, ydt, "y"), y_dtype,
@@ -175,7 +176,8 @@ def ptqtp_gemm_small(packed, x, N: int, K: int, group: int = 128, y_dtype: int =
 
 
 def ptqtp_gemm(packed, x, N: int, K: int, group: int = 128, y_dtype: int = PTQTP_F32, out=None):
-    """y [M,N] for x fp16 [M,K], any M up to 65536 (prefill uses the MFMA tile)."""
+    """y [M,N] for x fp16 [M,K], any M up to 65536 (prefill uses the MFMA tile; y_dtype | PTQTP_FUSED_PLANES
+    sums the planes in fp16 before the matrix pipe from 256 tokens on)."""
     if x.dim() != 2 or x.shape[1] != K:
         raise PtqtpError(2, "ptqtp_gemm")
     return _forward(_load().ptqtp_gemm, "ptqtp_gemm", packed, x, N, K, x.shape[0], group, y_dtype, out)

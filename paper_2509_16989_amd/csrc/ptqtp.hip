@@ -647,7 +647,11 @@ struct TileRecs {               // the records of a wave's four row tiles for on
 
 // MTW = token tiles per wave (4 or 8).  The four waves of a workgroup sit along the rows:
 // workgroup tile = 256 rows x 16*MTW tokens.
-template <int MTW>
+// FUSE: the two planes are summed before the matrix pipe, w16 = fp16(alpha1*t1 + alpha2*t2): both
+// products are exact in fp16, so this is ONE rounding per weight (the "dequantization" forward of
+// Sec. "Inference Efficiency": the weight is rebuilt, here per 32-column field in registers) and
+// half the MFMAs.
+template <int MTW, bool FUSE>
 __global__ void __launch_bounds__(256)
 gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB)
@@ -732,28 +736,46 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
                     al1[r] = half8{a1, a1, a1, a1, a1, a1, a1, a1};
                     al2[r] = half8{a2, a2, a2, a2, a2, a2, a2, a2};
                 }
-#pragma unroll
-                for (int fm = 0; fm < 4; ++fm) {
+                // software pipeline over the four 32-column fields of the group: while the MFMAs of
+                // field fm run, the operands of field fm+1 are read from LDS and its trits expanded
+                constexpr int NPL = FUSE ? 1 : 2;
+                half8 bq[2][NPL][4], aq[2][MTW];
+                auto expand = [&](half8 (&b)[NPL][4], int fm) {
                     const int wi = 2 * h + (fm >> 1), par = fm & 1;
-                    half8 b[2][4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        b[0][r] = decode8(cur.p1[r][wi], par) * al1[r];
-                        b[1][r] = decode8(cur.p2[r][wi], par) * al2[r];
+                        if constexpr (FUSE) {
+                            b[0][r] = decode8(cur.p1[r][wi], par) * al1[r] + decode8(cur.p2[r][wi], par) * al2[r];
+                        } else {
+                            b[0][r] = decode8(cur.p1[r][wi], par) * al1[r];
+                            b[NPL - 1][r] = decode8(cur.p2[r][wi], par) * al2[r];
+                        }
                     }
-                    half8 a[MTW];
+                };
+                auto operands = [&](half8 (&a)[MTW], int fm) {
 #pragma unroll
                     for (int mt = 0; mt < MTW; ++mt)
                         a[mt] = __builtin_bit_cast(
                             half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * kTileXStride + fm * 64));
+                };
+                // (measured: pays with one MFMA set per field; with two the plain order is as fast)
+                constexpr bool AHEAD = FUSE;
+                if (AHEAD) { operands(aq[0], 0); expand(bq[0], 0); }
+#pragma unroll
+                for (int fm = 0; fm < 4; ++fm) {
+                    if (!AHEAD) { operands(aq[fm & 1], fm); expand(bq[fm & 1], fm); }
+                    else if (fm + 1 < 4) {
+                        operands(aq[(fm + 1) & 1], fm + 1);
+                        expand(bq[(fm + 1) & 1], fm + 1);
+                    }
                     // consecutive MFMAs write different accumulators
 #pragma unroll
-                    for (int pl = 0; pl < 2; ++pl)
+                    for (int pl = 0; pl < NPL; ++pl)
 #pragma unroll
                         for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
                             for (int r = 0; r < 4; ++r)
-                                acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt], b[pl][r], acc[r][mt], 0, 0, 0);
+                                acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq[fm & 1][mt], bq[fm & 1][pl][r], acc[r][mt], 0, 0, 0);
                 }
                 if (more) {
                     char *d = xdst + ((g + 1) & 1) * (TM * kTileXStride);
@@ -959,7 +981,7 @@ hipError_t launch_gemm_tile2(const uint8_t *records, const uint16_t *x, void *y,
     return hipGetLastError();
 }
 
-template <int MTW>
+template <int MTW, bool FUSE>
 hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
                             hipStream_t stream)
 {
@@ -970,12 +992,12 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     const size_t lds = 2 * static_cast<size_t>(TM) * kTileXStride;
     static bool configured = false;                  // raise the dynamic LDS limit once per process
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<MTW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<MTW, FUSE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((gemm_tile_kernel<MTW>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
+    hipLaunchKernelGGL((gemm_tile_kernel<MTW, FUSE>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
                        static_cast<int>(s.KS), y_f16, MB, NB);
     return hipGetLastError();
@@ -1296,7 +1318,7 @@ hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int 
 }
 
 ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M,
-                         int64_t N, int64_t K, int32_t group, void *stream_, int64_t max_m)
+                         int64_t N, int64_t K, int32_t group, void *stream_, int64_t max_m, bool fuse_planes = false)
 {
     Shape s;
     ptqtp_status st;
@@ -1325,10 +1347,11 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
     } else if (M >= 256 || g_tune_tile == 1) {
         // 256-row x 128-token tiles leave CUs idle on small problems: use the 128 x 128 variant then
         const int64_t big_tiles = ((s.RT + 15) / 16) * ((M + 127) / 128);
-        if (g_tune_tile_variant == 2 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && big_tiles < 256))
+        if (!fuse_planes && (g_tune_tile_variant == 2 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && big_tiles < 256)))
             e = launch_gemm_tile2(records, x, y, Mi, s, f16, stream);
-        else if (M <= 64) e = launch_gemm_tile<4>(records, x, y, Mi, s, f16, stream);
-        else e = launch_gemm_tile<8>(records, x, y, Mi, s, f16, stream);
+        else if (M <= 64) e = launch_gemm_tile<4, false>(records, x, y, Mi, s, f16, stream);
+        else if (fuse_planes) e = launch_gemm_tile<8, true>(records, x, y, Mi, s, f16, stream);
+        else e = launch_gemm_tile<8, false>(records, x, y, Mi, s, f16, stream);
     } else if (M > PTQTP_GEMM_SMALL_MAX_M) {
         // 65..255 tokens: too few token blocks to fill the chip with 256-row tiles; run the
         // small-batch kernel on chunks of 64 tokens instead
@@ -1444,7 +1467,8 @@ ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, in
 ptqtp_status ptqtp_gemm(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M, int64_t N,
                         int64_t K, int32_t group, void *, size_t, void *stream)
 {
-    return run_forward(packed, x, y, y_dtype, M, N, K, group, stream, PTQTP_GEMM_MAX_M);
+    const bool fuse = (y_dtype & PTQTP_FUSED_PLANES) != 0 && M >= 256;
+    return run_forward(packed, x, y, y_dtype & ~PTQTP_FUSED_PLANES, M, N, K, group, stream, PTQTP_GEMM_MAX_M, fuse);
 }
 
 static ptqtp_status plan_items(const ptqtp_linear *linears, int32_t count, int32_t group, int64_t *total) {

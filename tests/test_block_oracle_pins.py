@@ -119,3 +119,27 @@ def test_round_half_against_numpy():
     # exact halves round to even
     assert oracle.round_half(np.array([1.0 + 2.0 ** -11]))[0] == 1.0
     assert oracle.round_half(np.array([1.0 + 3 * 2.0 ** -11]))[0] == 1.0 + 2.0 ** -9
+
+
+def test_forward_fused_pins():
+    # (a) within 2^-11 of the L1 bound of the unfused layer, and not identical to it on general scales
+    lin = workloads.make_linear(96, 512, 93, 1)
+    x = workloads.make_x(5, 512, 93, 2)
+    y, B = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
+    yf, Bf = oracle.forward_fused(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
+    assert np.all(np.abs(yf - y) <= 2.0 ** -11 * B * (1 + 1e-12))
+    assert np.abs(yf - y).max() > 0
+    # (b) scales whose sums are binary16 numbers: rounding changes nothing
+    lin2, x2 = workloads.integer_exact_case(48, 384, 3, 93, 3)
+    y2, _ = oracle.forward(lin2["T1"], lin2["T2"], lin2["a1"], lin2["a2"], x2)
+    y2f, _ = oracle.forward_fused(lin2["T1"], lin2["T2"], lin2["a1"], lin2["a2"], x2)
+    np.testing.assert_array_equal(y2f, y2)
+    # (c) one plane empty: the other plane's products are binary16 already
+    lin3 = dict(lin); lin3["T2"] = np.zeros_like(lin["T2"])
+    y3, _ = oracle.forward(lin3["T1"], lin3["T2"], lin3["a1"], lin3["a2"], x)
+    y3f, _ = oracle.forward_fused(lin3["T1"], lin3["T2"], lin3["a1"], lin3["a2"], x)
+    np.testing.assert_allclose(y3f, y3, rtol=1e-13, atol=1e-15)
+    # (d) against numpy's own rounding of the dense weight and a float64 matmul, entry by entry
+    W = oracle.reconstruct_dense(lin["T1"], lin["T2"], lin["a1"], lin["a2"])
+    ref = x.astype(np.float64) @ W.astype(np.float16).astype(np.float64).T
+    np.testing.assert_allclose(yf, ref, rtol=1e-13, atol=1e-15)

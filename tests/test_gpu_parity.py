@@ -396,6 +396,42 @@ def test_gemm_tile_forced_for_small_batches(ptq, M):
     check(y16, lin, x, tight=TIGHT_F16)
 
 
+@pytest.mark.parametrize("N,K,M", [(528, 2048, 256), (200, 1024, 300), (2048, 4096, 512), (16, 384, 257)])
+def test_gemm_fused_planes_matches_rounded_weight_oracle(ptq, N, K, M):
+    # PTQTP_FUSED_PLANES: the layer of the weight rounded once to fp16, exactly (tight gate), and inside the bar of the unfused layer
+    lin = workloads.make_linear(N, K, 73, N, K)
+    x = workloads.make_x(M, K, 73, N, M)
+    y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=ptq.PTQTP_F32 | ptq.PTQTP_FUSED_PLANES)
+    got = y.cpu().numpy().astype(np.float64)
+    ref_f, B_f = oracle.forward_fused(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
+    assert np.all(np.abs(got - ref_f) <= TIGHT * B_f), f"{(np.abs(got - ref_f) / B_f).max():.3e}"
+    ref, B = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+    assert np.all(np.abs(got - ref) <= TOL * B)
+    assert np.all(np.abs(got - ref) <= (2.0 ** -11 + TIGHT) * B)
+    # the flag really selects another arithmetic
+    y_plain = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K)
+    assert not torch.equal(y, y_plain)
+
+
+def test_gemm_fused_planes_integer_exact_and_small_m(ptq):
+    N, K, M = 272, 1024, 384
+    lin, x = workloads.integer_exact_case(N, K, M, 74)
+    y_ref, _ = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+    packed = pack(ptq, lin)
+    y = ptq.ptqtp_gemm(packed, dev(x), N, K, y_dtype=ptq.PTQTP_F32 | ptq.PTQTP_FUSED_PLANES)
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), y_ref)
+    y16 = ptq.ptqtp_gemm(packed, dev(x), N, K, y_dtype=ptq.PTQTP_F16 | ptq.PTQTP_FUSED_PLANES)
+    assert y16.dtype == torch.float16 and np.array_equal(y16.cpu().numpy().astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
+    # below 256 tokens the flag has no effect: same bits as without it
+    lin2 = workloads.make_linear(200, 640, 75)
+    x2 = workloads.make_x(40, 640, 75)
+    p2 = pack(ptq, lin2)
+    assert torch.equal(ptq.ptqtp_gemm(p2, dev(x2), 200, 640, y_dtype=ptq.PTQTP_FUSED_PLANES), ptq.ptqtp_gemm(p2, dev(x2), 200, 640))
+    # the other entry points do not take it
+    with pytest.raises(ptq.PtqtpError):
+        ptq.ptqtp_gemm_small(p2, dev(x2), 200, 640, y_dtype=ptq.PTQTP_FUSED_PLANES)
+
+
 def test_gemm_tile_integer_exact_and_general_scales(ptq):
     N, K, M = 272, 1536, 144
     lin, x = workloads.integer_exact_case(N, K, M, 72)
