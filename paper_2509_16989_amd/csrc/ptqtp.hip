@@ -459,24 +459,11 @@ hipError_t launch_items(const PlanHeader *plan, const LinearDesc &single, int y_
 // LDS operations of a wave execute in order, so the slot needs no barrier and is reused every step.
 // Token rows >= M re-load the last real token: their rows of D are garbage that is never stored
 // (rows of A only influence the same rows of D).
-#ifndef PTQTP_SLOT_LAYOUT
-#define PTQTP_SLOT_LAYOUT 0
-#endif
-#if PTQTP_SLOT_LAYOUT == 0
-// token-major: row r at r*528, chunk c at c*16
+// slot layout, token-major: row r at r*528, chunk c at c*16
 constexpr int kSlotRowBytes = 528;                   // 512 B of one token + 16 B pad: conflict-free operand reads
 constexpr int kSlotBytes = 16 * kSlotRowBytes;       // per wave
 __device__ __forceinline__ int slot_wr_off(int row, int chunk) { return row * kSlotRowBytes + chunk * 16; }
 __device__ __forceinline__ int slot_rd_off(int nl, int q, int f) { return nl * kSlotRowBytes + (f >> 2) * 256 + (f & 3) * 64 + q * 16; }
-#else
-// (field, quarter)-major: block j = f*4+q of 16 tokens x 16 B at j*272
-constexpr int kSlotBytes = 32 * 272;
-__device__ __forceinline__ int slot_wr_off(int row, int chunk) {
-    const int f = (chunk >> 4) * 4 + ((chunk >> 2) & 3), q = chunk & 3;
-    return (f * 4 + q) * 272 + row * 16;
-}
-__device__ __forceinline__ int slot_rd_off(int nl, int q, int f) { return (f * 4 + q) * 272 + nl * 16; }
-#endif
 
 // PLAN: the item list of a batch plan (R must be 1): one launch over many linears, all with M tokens.
 // ML = load instructions per 16-token tile (1, 2, 4 or 8): covers M <= 2*ML when MT == 1.
@@ -626,10 +613,7 @@ gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict
 // fp32 accumulator -- then issues 8*MTW MFMAs per 32-column field against MTW LDS operand reads.
 // Workgroups are numbered so that all token blocks of a row block run on the same XCD and
 // share its L2 copy of the packed rows.
-#ifndef PTQTP_TILE_STRIDE
-#define PTQTP_TILE_STRIDE 272
-#endif
-constexpr int kTileXStride = PTQTP_TILE_STRIDE;     // bytes per token row of the LDS x tile (128 fp16 + pad)
+constexpr int kTileXStride = 272;                   // bytes per token row of the LDS x tile (128 fp16 + pad)
 
 __device__ __forceinline__ half8 decode8(uint32_t word, int parity) {
     const uint32_t fp4 = (parity ? (word << 1) : word) & 0xAAAAAAAAu;

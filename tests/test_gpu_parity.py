@@ -535,6 +535,40 @@ def test_gemv_70b_shapes_sampled(ptq):
             _sampled_rows_check(ptq, lin, x32, y32, rows[:64])
 
 
+def test_batch_full_stack_as_benchmarked_sampled(ptq):
+    # the launch bench.py times: 32 layers x 7 linears of the 8B shapes in ONE plan; sampled rows of sampled linears
+    import bench
+    dev0 = torch.device("cuda:0")
+    blobs, xs, ys, jobs, dims, _ = bench.build_stack(ptq, torch, workloads, 32, dev0, log=False)
+    for y in ys:
+        y.fill_(float("nan"))
+    plan = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xs, ys, dims)])
+    ptq.ptqtp_gemv_batch(plan)
+    torch.cuda.synchronize()
+    assert all(bool(torch.isfinite(y).all()) for y in ys)            # every output of every linear was written
+    rng = np.random.default_rng(4)
+    picks = [(0, "q"), (0, "down"), (7, "k"), (15, "gate"), (31, "up"), (31, "down"), (31, "v")]
+    for layer, name in picks:
+        i = jobs.index((layer, name))
+        lin = workloads.linear_8b(name, layer)
+        N = lin["N"]
+        rows = np.unique(np.concatenate([np.arange(0, 16), np.arange(N - 16, N), rng.integers(0, N, 96)]))
+        _sampled_rows_check(ptq, lin, xs[i].cpu().numpy()[None, :], ys[i], rows)
+    # the same stack at 16 tokens per linear through the batched small-batch kernel
+    M = 16
+    xm = [torch.from_numpy(workloads.x_for(name, M, k, 2, layer)).to(dev0) for (layer, name), (n, k) in zip(jobs, dims)]
+    ym = [torch.full((M, n), float("nan"), dtype=torch.float32, device=dev0) for (n, k) in dims]
+    planm = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xm, ym, dims)])
+    ptq.ptqtp_gemm_batch(planm, M)
+    torch.cuda.synchronize()
+    assert all(bool(torch.isfinite(y).all()) for y in ym)
+    for layer, name in picks[1::2]:
+        i = jobs.index((layer, name))
+        lin = workloads.linear_8b(name, layer)
+        rows = np.unique(rng.integers(0, lin["N"], 64))
+        _sampled_rows_check(ptq, lin, xm[i].cpu().numpy(), ym[i], rows)
+
+
 def test_smoke_entry(ptq):
     import __graft_entry__
     __graft_entry__.smoke()
