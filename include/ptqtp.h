@@ -266,7 +266,8 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
  * wave: 1, 2 or 4), "small_items" (batch > 1: 1 = item kernel, 0 = tiled kernel,
  * -1 = default), "small_waves" (waves per item for batch > 1, 1..8), "tile"
  * (1 = use the MFMA tile for every batch > 1, -1 = default), "tile_variant" (1 = always the
- * 256 x 128 tile, 2 = always the 128 x 128 two-waves-per-SIMD tile, 0 = default: by problem size), "small_rows" (row tiles per item of
+ * 256 x 128 tile, 2 = always the 128 x 128 two-waves-per-SIMD tile, 3 = always the 256 x 256 tile with direct-to-LDS
+ * activation loads, 0 = default: by problem size), "small_rows" (row tiles per item of
  * the small-batch kernel, 1 or 2), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation
  * loads, -1/1 = shared activation tile), "small_fold" (ptqtp_gemm_batch with two row tiles per wave:
  * 1 = multiply the group scales into the expanded trits before the matrix pipe, 0 = rescale the

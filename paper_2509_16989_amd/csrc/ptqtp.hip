@@ -944,6 +944,180 @@ gemm_tile2_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
     }
 }
 
+// Large prefill tile: workgroup = 4 x 2 waves (two per SIMD), each 4 row tiles x 8 token tiles:
+// 256 rows x 256 tokens.  Twice the tokens per decoded trit of the 128-token tiles at the same
+// L1 traffic per MFMA, and a second wave on every SIMD to fill the issue slots the first one
+// leaves.  What makes it fit in 256 registers per lane:
+//  - activations go from global memory straight into LDS (global_load_lds_dwordx4, no staging
+//    registers).  One instruction moves a 1-KiB chunk = the 256 bytes (one 128-column group) of
+//    four tokens, lane t*16+p bringing 16-byte piece p of token t -- four full 256-byte runs, the
+//    pattern the L1 serves at full rate (16 tokens x 64 bytes per instruction runs 4x slower).
+//    Chunk c of a 64-token block holds tokens c, c+16, c+32, c+48 and starts at c*1040 bytes, so
+//    the 16 tokens of an MFMA token tile sit in 16 different chunks, each skewed by 16 bytes:
+//    the A-operand read (token nl, pieces 4*field+q) is one conflict-free ds_read_b128;
+//  - record words are fetched per scale group, 8 bytes per lane, plane and row tile.
+// FUSE as in gemm_tile_kernel.
+constexpr int kTile3Tokens = 256;
+constexpr int kTile3Chunk = 1040;                             // 1 KiB + 16-byte skew
+constexpr int kTile3BufBytes = 64 * kTile3Chunk;              // one 128-column group of 256 tokens
+
+template <bool FUSE>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
+                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB)
+{
+    extern __shared__ char xt[];                     // [2][64 chunks][1040]
+    constexpr int TM = kTile3Tokens, NRT = 16;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nl = lane & 15, q = lane >> 4;
+    const int wm = w & 1, wn = w >> 1;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int nb = (slot / MB) * 8 + xcd, mb = slot % MB;
+    if (nb >= NB) return;                            // whole workgroup, before any barrier
+    const int m0 = mb * TM;
+    const int rt_base = nb * NRT + wn * 4;
+    const int NG = K / 128;
+
+    // staging role: wave w brings in chunks 8*(w%2) .. +7 of 64-token block w/2; lane t*16+p: piece p of token c + 16*t
+    const int tok0 = m0 + (w >> 1) * 64 + (w & 1) * 8 + (lane >> 4) * 16;
+    const uint16_t *xcol = x + (lane & 15) * 8;
+    auto stage = [&](int g, int buf) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            int m = tok0 + j;
+            m = m < M ? m : M - 1;                   // rows past M: duplicates, never stored
+            asm volatile("" : "+v"(m));              // recompute the row address here: eight hoisted 64-bit addresses would not fit
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(xcol + static_cast<size_t>(m) * K + g * 128),
+                (__attribute__((address_space(3))) void *)(xt + buf * kTile3BufBytes + ((w >> 1) * 16 + (w & 1) * 8 + j) * kTile3Chunk),
+                16, 0, 0);
+        }
+    };
+
+    const uint8_t *rec[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        int rt = rt_base + r;
+        rt = rt < RT ? rt : RT - 1;
+        rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes + lane * 16;
+    }
+
+    floatx4 acc[4][8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // words of group g: record g/2, half g%2 -> 8 bytes per lane, plane and row tile; scales: 4 fp16 per row
+    auto load_group = [&](uintx2 (&pw)[4][2], uintx2 (&sc)[4], int g) {
+        const size_t off = static_cast<size_t>(g >> 1) * kRecordBytes + (g & 1) * 8;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            pw[r][0] = load_global<uintx2>(rec[r] + off);
+            pw[r][1] = load_global<uintx2>(rec[r] + off + kPlaneBytes);
+            sc[r] = load_global<uintx2>(rec[r] - lane * 16 + static_cast<size_t>(g >> 1) * kRecordBytes + 2 * kPlaneBytes + nl * 8);
+        }
+    };
+    auto compute = [&](const uintx2 (&pw)[4][2], const uintx2 (&sc)[4], int g) {
+        // token tile mt of this wave: 64-token block 2*wm + mt/4, tokens (mt%4)*16 + nl -> chunk nl, run mt%4
+        const char *xb = xt + (g & 1) * kTile3BufBytes + wm * (32 * kTile3Chunk) + nl * kTile3Chunk + q * 16;
+        const int h = g & 1;
+        constexpr int NPL = FUSE ? 1 : 2;
+        half8 al[4][2];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].x >> 16) : (sc[r].x & 0xffffu)));
+            const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].y >> 16) : (sc[r].y & 0xffffu)));
+            al[r][0] = half8{a1, a1, a1, a1, a1, a1, a1, a1};
+            al[r][1] = half8{a2, a2, a2, a2, a2, a2, a2, a2};
+        }
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm) {
+            half8 b[NPL][4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const half8 t1 = decode8((fm >> 1) ? pw[r][0].y : pw[r][0].x, fm & 1) * al[r][0];
+                const half8 t2 = decode8((fm >> 1) ? pw[r][1].y : pw[r][1].x, fm & 1) * al[r][1];
+                if constexpr (FUSE) { b[0][r] = t1 + t2; } else { b[0][r] = t1; b[NPL - 1][r] = t2; }
+            }
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                const half8 a = __builtin_bit_cast(
+                    half8, *reinterpret_cast<const uintx4 *>(xb + (mt >> 2) * (16 * kTile3Chunk) + (mt & 3) * 256 + fm * 64));
+#pragma unroll
+                for (int pl = 0; pl < NPL; ++pl)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[pl][r], acc[r][mt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);       // keep the next field's expansion out of this one's registers
+        }
+    };
+
+    uintx2 pa[4][2], pb[4][2], sa[4], sb[4];
+    stage(0, 0);
+    load_group(pa, sa, 0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { pb[r][0] = pa[r][0]; pb[r][1] = pa[r][1]; sb[r] = sa[r]; }
+    __builtin_amdgcn_s_waitcnt(0);                   // this wave's chunks have landed in LDS
+    __syncthreads();
+
+    for (int g = 0; g < NG; g += 2) {
+        const bool m1 = g + 1 < NG, m2 = g + 2 < NG;
+        if (m1) { stage(g + 1, 1); load_group(pb, sb, g + 1); }
+        compute(pa, sa, g);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (m1) {
+            if (m2) { stage(g + 2, 0); load_group(pa, sa, g + 2); }
+            compute(pb, sb, g + 1);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int rt = rt_base + r;
+        const int n = rt * kTileRows + nl;
+        if (rt < RT && n < N) {
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int m = m0 + wm * 128 + mt * 16 + 4 * q + j;
+                    if (m < M) {
+                        const size_t off = static_cast<size_t>(m) * N + n;
+                        if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(acc[r][mt][j]);
+                        else reinterpret_cast<float *>(y)[off] = acc[r][mt][j];
+                    }
+                }
+        }
+    }
+}
+
+template <bool FUSE>
+hipError_t launch_gemm_tile3(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
+                             hipStream_t stream)
+{
+    const int MB = (M + kTile3Tokens - 1) / kTile3Tokens;
+    const int NB = static_cast<int>((s.RT + 15) / 16);
+    const int64_t grid = static_cast<int64_t>((NB + 7) / 8) * 8 * MB;
+    const size_t lds = 2 * static_cast<size_t>(kTile3BufBytes);
+    static bool configured = false;                  // raise the dynamic LDS limit once per process
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile3_kernel<FUSE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((gemm_tile3_kernel<FUSE>), dim3(static_cast<unsigned>(grid)), dim3(512), lds, stream, records, x,
+                       y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
+                       static_cast<int>(s.KS), y_f16, MB, NB);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm_tile2(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
                              hipStream_t stream)
 {
@@ -1331,7 +1505,15 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
     } else if (M >= 256 || g_tune_tile == 1) {
         // 256-row x 128-token tiles leave CUs idle on small problems: use the 128 x 128 variant then
         const int64_t big_tiles = ((s.RT + 15) / 16) * ((M + 127) / 128);
-        if (!fuse_planes && (g_tune_tile_variant == 2 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && big_tiles < 256)))
+        // 256 x 256 tiles do ~15 % more work per second than 256 x 128 ones but need enough of them to fill the
+        // 256 CUs in whole rounds: compare the two by (speed x fraction of the last round's CUs that are busy)
+        const int64_t t3 = ((s.RT + 15) / 16) * ((M + 255) / 256);
+        const double eff3 = 1.15 * static_cast<double>(t3) / static_cast<double>((t3 + 255) / 256 * 256);
+        const double eff1 = static_cast<double>(big_tiles) / static_cast<double>((big_tiles + 255) / 256 * 256);
+        if (g_tune_tile_variant == 3 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && M >= 256 && eff3 >= eff1))
+            e = fuse_planes ? launch_gemm_tile3<true>(records, x, y, Mi, s, f16, stream)
+                            : launch_gemm_tile3<false>(records, x, y, Mi, s, f16, stream);
+        else if (!fuse_planes && (g_tune_tile_variant == 2 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && big_tiles < 256)))
             e = launch_gemm_tile2(records, x, y, Mi, s, f16, stream);
         else if (M <= 64) e = launch_gemm_tile<4, false>(records, x, y, Mi, s, f16, stream);
         else if (fuse_planes) e = launch_gemm_tile<8, true>(records, x, y, Mi, s, f16, stream);
@@ -1574,7 +1756,7 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
         return PTQTP_OK;
     }
     if (!strcmp(key, "tile_variant")) {
-        if (value < 0 || value > 2) return PTQTP_ERR_SHAPE;
+        if (value < 0 || value > 3) return PTQTP_ERR_SHAPE;
         g_tune_tile_variant = value;
         return PTQTP_OK;
     }

@@ -372,13 +372,18 @@ def test_gemm_tile_variants(ptq, N, K, M):
     lin = workloads.make_linear(N, K, 73, N, K)
     x = workloads.make_x(M, K, 73, N, M)
     packed = pack(ptq, lin)
-    for variant in (1, 2):                         # 256 x 128 tile, 128 x 128 tile
+    ys = []
+    for variant in (1, 2, 3):                      # 256 x 128 tile, 128 x 128 tile, 256 x 256 tile
         try:
             ptq.ptqtp_tune("tile_variant", variant)
-            y = ptq.ptqtp_gemm(packed, dev(x), N, K)
+            y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+            ptq.ptqtp_gemm(packed, dev(x), N, K, out=y)
         finally:
             ptq.ptqtp_tune("tile_variant", 0)
         check(y, lin, x, tight=3e-5)
+        ys.append(y)
+    # every tile feeds each accumulator the same MFMA sequence: identical bits
+    assert torch.equal(ys[0], ys[1]) and torch.equal(ys[0], ys[2])
 
 
 @pytest.mark.parametrize("M", [2, 16, 33, 64])
@@ -401,13 +406,19 @@ def test_gemm_fused_planes_matches_rounded_weight_oracle(ptq, N, K, M):
     # PTQTP_FUSED_PLANES: the layer of the weight rounded once to fp16, exactly (tight gate), and inside the bar of the unfused layer
     lin = workloads.make_linear(N, K, 73, N, K)
     x = workloads.make_x(M, K, 73, N, M)
-    y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=ptq.PTQTP_F32 | ptq.PTQTP_FUSED_PLANES)
-    got = y.cpu().numpy().astype(np.float64)
     ref_f, B_f = oracle.forward_fused(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
-    assert np.all(np.abs(got - ref_f) <= TIGHT * B_f), f"{(np.abs(got - ref_f) / B_f).max():.3e}"
     ref, B = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
-    assert np.all(np.abs(got - ref) <= TOL * B)
-    assert np.all(np.abs(got - ref) <= (2.0 ** -11 + TIGHT) * B)
+    for variant in (0, 1, 3):                      # default choice, 256 x 128 tile, 256 x 256 tile
+        try:
+            ptq.ptqtp_tune("tile_variant", variant)
+            y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+            ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=ptq.PTQTP_F32 | ptq.PTQTP_FUSED_PLANES, out=y)
+        finally:
+            ptq.ptqtp_tune("tile_variant", 0)
+        got = y.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - ref_f) <= TIGHT * B_f), f"{(np.abs(got - ref_f) / B_f).max():.3e}"
+        assert np.all(np.abs(got - ref) <= TOL * B)
+        assert np.all(np.abs(got - ref) <= (2.0 ** -11 + TIGHT) * B)
     # the flag really selects another arithmetic
     y_plain = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K)
     assert not torch.equal(y, y_plain)
@@ -447,18 +458,26 @@ def test_gemm_tile_integer_exact_and_general_scales(ptq):
     check(ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K), lin, x, tight=3e-5)
 
 
-def test_gemm_tile_prefill_70b_sampled(ptq):
-    # prefill M = 2048 on a 70B-shaped k/v projection; sampled rows and tokens against the oracle
-    lin = workloads.linear_70b("k")
+@pytest.mark.parametrize("name,flag", [("k", 0), ("q", 0), ("q", 16)])
+def test_gemm_tile_prefill_70b_sampled(ptq, name, flag):
+    # prefill M = 2048 on 70B-shaped projections (k: 1024 rows, the 128 x 128 tile; q: 8192 rows, the 256 x 256 tile,
+    # also with fused planes); sampled rows and tokens against the oracle
+    lin = workloads.linear_70b(name)
     N, K, M = lin["N"], lin["K"], 2048
-    x = workloads.x_for("k", M, K, config=4)
-    y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K)
-    rows = np.unique(np.random.default_rng(4).integers(0, N, 48))
-    toks = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 2047], np.random.default_rng(5).integers(0, M, 24)]))
-    ref, B = oracle.forward(lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows], x[toks], threads=8)
+    x = workloads.x_for(name, M, K, config=4)
+    y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=flag)
+    rows = np.unique(np.concatenate([[0, 15, N - 1], np.random.default_rng(4).integers(0, N, 48)]))
+    toks = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 255, 256, 2047], np.random.default_rng(5).integers(0, M, 24)]))
+    sub = (lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows])
+    ref, B = oracle.forward(*sub, x[toks], threads=8)
     got = y.cpu().numpy().astype(np.float64)[np.ix_(toks, rows)]
     err = np.abs(got - ref)
-    assert np.all(err <= TOL * B) and np.all(err <= 3e-5 * B), f"{(err / B).max():.3e}"
+    assert np.all(err <= TOL * B)
+    if flag:
+        ref_f, B_f = oracle.forward_fused(*sub, x[toks])
+        assert np.all(np.abs(got - ref_f) <= 3e-5 * B_f)
+    else:
+        assert np.all(err <= 3e-5 * B), f"{(err / B).max():.3e}"
 
 
 def test_gemm_small_rows_match_gemv(ptq):
