@@ -282,6 +282,11 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
                 if M == 2048:
                     ent["TFLOPs"] = round(4.0 * M * n * k / us / 1e6, 1)      # two planes: 2*2*M*N*K
                 res["70b"][f"{name}_{n}x{k}_M{M}"] = ent
+                if M == 2048:
+                    # planes summed in fp16 before the matrix pipe (one more rounding per weight, half the MFMAs)
+                    flag = ptq.PTQTP_F32 | ptq.PTQTP_FUSED_PLANES
+                    us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blob, x, n, k, out=y, y_dtype=flag) for _ in range(4)], 4, reps=5)
+                    res["70b"][f"{name}_{n}x{k}_M{M}_fused_planes"] = {"us": round(us, 2), "TFLOPs_counted_as_two_planes": round(4.0 * M * n * k / us / 1e6, 1)}
             del blob
         # config 2 on the whole stack: one batched launch per step, M tokens per linear
         res["stack_batched"] = {}
