@@ -186,7 +186,8 @@ def main() -> int:
                 others[mode] = round(time_steps(torch, st, max(3, args.steps // 5), 2, stream) * 1e3, 2)
         extra["us_per_decode_step_other_modes"] = others
         if args.per_shape:
-            extra["per_shape"] = per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, args.no_cpu_baseline)
+            extra["per_shape"] = per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, args.no_cpu_baseline,
+                                                  quick=args.steps < 50)
 
     gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
     launch_us = ms_per_step * 1e3 / launches_step
@@ -248,7 +249,7 @@ def _graph_time(torch, stream, run, launches, reps=10):
     return e0.elapsed_time(e1) * 1e3 / (reps * launches)
 
 
-def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False):
+def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False, quick=False):
     """The other BASELINE configs, one linear per launch (not the headline):
     config 1/2: each 8B shape at M = 1, 4, 16, 64, cold (walking the 32 layer copies) -- and M = 1 hot;
     config 4:   70B shapes at M = 1 and 32 (hot: one copy) and prefill M = 2048 on the MFMA tile;
@@ -256,6 +257,10 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
     import workloads
     res = {"8b": {}, "70b": {}}
     dev = xs[0].device
+    reps = 2 if quick else 10              # quick: few replays, for runs under a profiler (chosen by --steps < 50)
+
+    def note(what):
+        print(f"[bench] per-shape: {what}", file=sys.stderr, flush=True)
     with torch.cuda.stream(stream):
         for name in ("q", "k", "gate", "down"):
             idxs = [i for i, j in enumerate(jobs) if j[1] == name]
@@ -263,11 +268,12 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
             for M in (1, 4, 16, 64):
                 x = torch.randn(M, k, device=dev).half()
                 y = torch.empty(M, n, device=dev)
-                us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blobs[i], x, n, k, out=y) for i in idxs], len(idxs))
+                us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blobs[i], x, n, k, out=y) for i in idxs], len(idxs), reps=reps)
                 res["8b"][f"{name}_{n}x{k}_M{M}_cold"] = {"us": round(us, 2), "GBps": round(algorithmic_bytes(n, k, M) / us / 1e3, 1)}
             x = xs[idxs[0]].reshape(1, -1)
             y = ys[idxs[0]]
-            us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blobs[idxs[0]], x, n, k, out=y) for _ in range(32)], 32)
+            us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blobs[idxs[0]], x, n, k, out=y) for _ in range(32)], 32, reps=reps)
+            note(f"8B {name} done")
             res["8b"][f"{name}_{n}x{k}_M1_hot"] = {"us": round(us, 2), "GBps": round(algorithmic_bytes(n, k, 1) / us / 1e3, 1)}
         for name in ("q", "k", "gate", "down"):
             lin = workloads.linear_70b(name)
@@ -277,7 +283,7 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
             for M in (1, 32, 2048):
                 x = torch.randn(M, k, device=dev).half()
                 y = torch.empty(M, n, device=dev)
-                us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blob, x, n, k, out=y) for _ in range(4)], 4, reps=5)
+                us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blob, x, n, k, out=y) for _ in range(4)], 4, reps=min(reps, 5))
                 ent = {"us": round(us, 2), "GBps": round(algorithmic_bytes(n, k, M) / us / 1e3, 1)}
                 if M == 2048:
                     ent["TFLOPs"] = round(4.0 * M * n * k / us / 1e6, 1)      # two planes: 2*2*M*N*K
@@ -285,9 +291,10 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
                 if M == 2048:
                     # planes summed in fp16 before the matrix pipe (one more rounding per weight, half the MFMAs)
                     flag = ptq.PTQTP_F32 | ptq.PTQTP_FUSED_PLANES
-                    us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blob, x, n, k, out=y, y_dtype=flag) for _ in range(4)], 4, reps=5)
+                    us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blob, x, n, k, out=y, y_dtype=flag) for _ in range(4)], 4, reps=min(reps, 5))
                     res["70b"][f"{name}_{n}x{k}_M{M}_fused_planes"] = {"us": round(us, 2), "TFLOPs_counted_as_two_planes": round(4.0 * M * n * k / us / 1e6, 1)}
             del blob
+            note(f"70B {name} done")
         # config 2 on the whole stack: one batched launch per step, M tokens per linear
         res["stack_batched"] = {}
         for M in (4, 16, 64):
@@ -295,14 +302,16 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
             ym = [torch.empty(M, n, device=dev) for (n, k) in dims]
             plan = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xm, ym, dims)])
             stream.synchronize()
-            ms = time_steps(torch, lambda: ptq.ptqtp_gemm_batch(plan, M), 30, 10, stream)
+            ms = time_steps(torch, lambda: ptq.ptqtp_gemm_batch(plan, M), 5 if quick else 30, 2 if quick else 10, stream)
+            note(f"stack at M={M} done")
             nbytes = sum(algorithmic_bytes(n, k, M) for n, k in dims)
             res["stack_batched"][f"M{M}"] = {"us_per_step": round(ms * 1e3, 1), "GBps": round(nbytes / ms / 1e6, 1)}
             del xm, ym, plan
         # config 3 with the activations really depending on each other: per layer qkv -> o (+residual) ->
         # gate|up (silu(gate)*up) -> down (+residual), fp16 activations, one launch per stage (128 launches)
         # replayed from a hipGraph.  Attention itself is not part of the path: o reads the q part of qkv's output.
-        res["dependent_chain"] = dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream)
+        res["dependent_chain"] = dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream, quick)
+        note("dependent chain done")
         # the step before the path: PTQTP decomposition of Gaussian fp16 weights (paper settings: T_max 50, eps 1e-4)
         res["quantize"] = {}
         for name in ("q", "gate"):
@@ -329,7 +338,7 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
     return res
 
 
-def dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream):
+def dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream, quick=False):
     """Fuse the stack's q|k|v and gate|up blobs on the device (unpack, stack the rows, pack), build the
     decode chain over all layers and time one step.  The scales of o and down are multiplied by 1/8 and 1/32
     (exact in fp16) so that the residual stream of 32 random layers stays finite."""
@@ -374,7 +383,7 @@ def dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream):
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=stream):
         ptq.ptqtp_chain_run(plan)
-    ms = time_steps(torch, lambda: g.replay(), 100, 20, stream)
+    ms = time_steps(torch, lambda: g.replay(), 5 if quick else 100, 2 if quick else 20, stream)
     return {"us_per_step": round(ms * 1e3, 1), "GBps": round(nbytes / ms / 1e6, 1), "launches": len(stages),
             "layers": layers, "output_finite": finite}
 
