@@ -554,6 +554,22 @@ def test_gemv_70b_shapes_sampled(ptq):
             _sampled_rows_check(ptq, lin, x32, y32, rows[:64])
 
 
+@pytest.mark.parametrize("N,K", [(262144, 128), (16, 262144), (1, 128), (100000, 384)])
+def test_extreme_aspect_ratios_sampled(ptq, N, K):
+    # very tall, very wide and the smallest layer: index arithmetic at both ends (sampled rows, batch 1, 5 and 300)
+    lin = workloads.make_linear(N, K, 76, N % 1000, K % 1000)
+    packed = pack(ptq, lin)
+    rows = np.unique(np.concatenate([np.arange(0, min(N, 17)), np.arange(max(0, N - 17), N),
+                                     np.random.default_rng(6).integers(0, N, 64)]))
+    for M in (1, 5, 300):
+        if M * (N + K) > 40_000_000:
+            continue
+        x = workloads.make_x(M, K, 76, M)
+        y = ptq.ptqtp_gemm(packed, dev(x), N, K)
+        assert bool(torch.isfinite(y).all())
+        _sampled_rows_check(ptq, lin, x, y, rows)
+
+
 def test_batch_full_stack_as_benchmarked_sampled(ptq):
     # the launch bench.py times: 32 layers x 7 linears of the 8B shapes in ONE plan; sampled rows of sampled linears
     import bench
