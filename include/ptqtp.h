@@ -259,19 +259,15 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
 
 /*
  * Tuning hook for benchmarks and sweeps (not needed for correct use): override
- * the launch shape the compute calls pick.  key = "gemv_waves" (waves per
- * workgroup, 1..16), "gemv_rows" (16-row tiles per workgroup, 1, 2 or 4),
- * "gemv_stream" (batch 1: 1 = item kernel, 0 = tiled kernel, -1 = default),
- * "stream_waves" (waves per item, 1..16), "stream_depth" (records in flight per
- * wave: 1, 2 or 4), "small_items" (batch > 1: 1 = item kernel, 0 = tiled kernel,
- * -1 = default), "small_waves" (waves per item for batch > 1, 1..8), "tile"
- * (1 = use the MFMA tile for every batch > 1, -1 = default), "tile_variant" (1 = always the
- * 256 x 128 tile, 2 = always the 128 x 128 two-waves-per-SIMD tile, 3 = always the 256 x 256 tile with direct-to-LDS
- * activation loads, 0 = default: by problem size), "small_rows" (row tiles per item of
- * the small-batch kernel, 1 or 2), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation
- * loads, -1/1 = shared activation tile), "small_fold" (ptqtp_gemm_batch with two row tiles per wave:
- * 1 = multiply the group scales into the expanded trits before the matrix pipe, 0 = rescale the
- * per-group sums after it, -1 = default: before for more than 16 tokens);
+ * the launch shape the compute calls pick.  key = "stream_waves" (batch 1: waves per item, 1..16),
+ * "stream_depth" (batch 1: records in flight per wave: 1, 2 or 4), "small_waves" (one linear at batch > 1:
+ * waves per item, 1..8), "small_rows" (row tiles per item / per wave of the small-batch kernels, 1 or 2),
+ * "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation loads, -1/1 = shared activation tile),
+ * "small_fold" (ptqtp_gemm_batch with two row tiles per wave: 1 = multiply the group scales into the
+ * expanded trits before the matrix pipe, 0 = rescale the per-group sums after it, -1 = default: before for
+ * more than 16 tokens), "tile" (1 = use an MFMA tile for every batch > 1, -1 = default), "tile_variant"
+ * (1 = always the 256 x 128 tile, 2 = always the 128 x 128 two-waves-per-SIMD tile, 3 = always the
+ * 256 x 256 tile with direct-to-LDS activation loads, 0 = default: by problem size);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
  * unknown key or out-of-range value.  Not thread-safe.
  */

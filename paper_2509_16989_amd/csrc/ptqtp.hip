@@ -162,124 +162,6 @@ unpack_scales_kernel(const uint8_t *__restrict__ blob, uint16_t *__restrict__ a1
 // ------------------------------------------------------------------------------------------
 // streamed GEMV / small-batch GEMM on the matrix pipe
 // ------------------------------------------------------------------------------------------
-// Workgroup = W waves sharing R consecutive 16-row tiles; wave w takes the 256-column steps
-// ks = w, w+W, ...  Lane l = q*16 + nl: as MFMA A operand it carries token (mt*16 + nl), as B
-// operand row (rt*16 + nl), both for the same 8 columns per MFMA; the result D has token
-// 4q+j (j = 0..3) of row nl in register j.  SINGLE is the batch-1 path: only token 0 is
-// loaded and only register 0 of lanes 0..15 is kept.
-template <int MT, int R, bool SINGLE>
-__global__ void __launch_bounds__(MT == 1 ? 1024 : 512)
-gemv_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
-            int M, int N, int K, int RT, int KS, int y_f16)
-{
-    extern __shared__ float red[];
-    constexpr int MR = SINGLE ? 1 : 4;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, W = blockDim.x >> 6;
-    const int nl = lane & 15, q = lane >> 4;
-    const int rt0 = blockIdx.x * R;
-
-    float yacc[R][MT][MR];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int j = 0; j < MR; ++j) yacc[r][mt][j] = 0.f;
-
-    for (int ks = w; ks < KS; ks += W) {
-        // weights first: they come from HBM and have the longest latency
-        uintx4 p1[R], p2[R];
-        uintx2 sc[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int rt = rt0 + r;
-            if (rt < RT) {
-                const uint8_t *rec = records + (static_cast<size_t>(rt) * KS + ks) * kRecordBytes;
-                p1[r] = *reinterpret_cast<const uintx4 *>(rec + lane * 16);
-                p2[r] = *reinterpret_cast<const uintx4 *>(rec + kPlaneBytes + lane * 16);
-                sc[r] = *reinterpret_cast<const uintx2 *>(rec + 2 * kPlaneBytes + nl * 8);
-            } else {
-                p1[r] = uintx4{0, 0, 0, 0}; p2[r] = uintx4{0, 0, 0, 0}; sc[r] = uintx2{0, 0};
-            }
-        }
-        // activations for this step (L2-resident): lane (token nl, quarter q), 8 columns per field
-        uintx4 xa[MT][8];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int m = mt * 16 + nl;
-            const bool live = SINGLE ? (nl == 0) : (m < M);
-#pragma unroll
-            for (int f = 0; f < 8; ++f) {
-                const int k0 = ks * kStepK + (f >> 2) * 128 + (f & 3) * 32 + q * 8;
-                xa[mt][f] = uintx4{0, 0, 0, 0};
-                if (live && k0 < K)
-                    xa[mt][f] = *reinterpret_cast<const uintx4 *>(x + static_cast<size_t>(m) * K + k0);
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const float a1g0 = half_bits_to_float(sc[r].x & 0xffffu), a1g1 = half_bits_to_float(sc[r].x >> 16);
-            const float a2g0 = half_bits_to_float(sc[r].y & 0xffffu), a2g1 = half_bits_to_float(sc[r].y >> 16);
-            floatx4 acc[MT];
-            group_sum<MT, 0>(xa, p1[r], acc);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int j = 0; j < MR; ++j) yacc[r][mt][j] = fmaf(a1g0, acc[mt][j], yacc[r][mt][j]);
-            group_sum<MT, 1>(xa, p1[r], acc);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int j = 0; j < MR; ++j) yacc[r][mt][j] = fmaf(a1g1, acc[mt][j], yacc[r][mt][j]);
-            group_sum<MT, 0>(xa, p2[r], acc);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int j = 0; j < MR; ++j) yacc[r][mt][j] = fmaf(a2g0, acc[mt][j], yacc[r][mt][j]);
-            group_sum<MT, 1>(xa, p2[r], acc);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int j = 0; j < MR; ++j) yacc[r][mt][j] = fmaf(a2g1, acc[mt][j], yacc[r][mt][j]);
-        }
-    }
-
-    // cross-wave reduction in LDS, fixed order => bit-identical run to run
-    constexpr int OUT = SINGLE ? R * 16 : R * MT * 256;   // partials per wave
-    if (SINGLE) {
-        if (q == 0) {
-#pragma unroll
-            for (int r = 0; r < R; ++r) red[w * OUT + r * 16 + nl] = yacc[r][0][0];
-        }
-    } else {
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    red[w * OUT + ((r * MT + mt) * 16 + 4 * q + j) * 16 + nl] = yacc[r][mt][j];
-    }
-    __syncthreads();
-    for (int o = threadIdx.x; o < OUT; o += blockDim.x) {
-        float s = 0.f;
-        for (int ww = 0; ww < W; ++ww) s += red[ww * OUT + o];
-        int r, m;
-        const int on = o & 15;
-        if (SINGLE) { r = o >> 4; m = 0; }
-        else { const int t = o >> 4; m = (t / 16 % MT) * 16 + (t & 15); r = t / (16 * MT); }
-        const int n = (rt0 + r) * kTileRows + on;
-        if (m < M && n < N) {
-            const size_t off = static_cast<size_t>(m) * N + n;
-            if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(s);
-            else reinterpret_cast<float *>(y)[off] = s;
-        }
-    }
-}
-
-
-// ------------------------------------------------------------------------------------------
-// batch-1 kernel over a list of (linear, 16-row tile) items
 // ------------------------------------------------------------------------------------------
 // One workgroup = one item = one 16-row tile of one linear over its whole K.  Its W waves split
 // the item's 256-column steps (wave w: ks = w, w+W, ...).  A wave issues the loads of up to S
@@ -424,7 +306,6 @@ gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int si
     }
 }
 
-int g_tune_stream = -1;      // -1/1: item kernel for batch 1, 0: tiled kernel
 int g_tune_stream_waves = 0, g_tune_stream_depth = 0;
 
 template <bool PLAN>
@@ -1161,7 +1042,7 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     return hipGetLastError();
 }
 
-int g_tune_small_waves = 0, g_tune_small = -1, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0, g_tune_small_fold = -1;
+int g_tune_small_waves = 0, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0, g_tune_small_fold = -1;
 
 template <int MT, int R, int S, bool PLAN, int ML>
 hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
@@ -1436,28 +1317,6 @@ hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStr
     return hipGetLastError();
 }
 
-int g_tune_waves = 0, g_tune_rows = 0;
-
-template <int MT, int R, bool SINGLE>
-hipError_t launch_gemv(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s,
-                       int W, int y_f16, hipStream_t stream)
-{
-    const int grid = static_cast<int>((s.RT + R - 1) / R);
-    const size_t lds = static_cast<size_t>(W) * (SINGLE ? R * 16 : R * MT * 256) * sizeof(float);
-    hipLaunchKernelGGL((gemv_kernel<MT, R, SINGLE>), dim3(grid), dim3(W * 64), lds, stream, records, x, y, M,
-                       static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
-                       static_cast<int>(s.KS), y_f16);
-    return hipGetLastError();
-}
-
-// Waves per workgroup: the fewest waves that reach the minimal number of steps per wave.
-int pick_waves(int64_t KS, int wmax) {
-    if (g_tune_waves > 0) return g_tune_waves < wmax ? g_tune_waves : wmax;
-    const int64_t per = (KS + wmax - 1) / wmax;
-    int W = static_cast<int>((KS + per - 1) / per);
-    return W < 1 ? 1 : W;
-}
-
 // 2..64 tokens: the small-batch item kernel in the shape that measured best
 hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int f16,
                         hipStream_t stream)
@@ -1489,19 +1348,13 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
     const uint8_t *records = static_cast<const uint8_t *>(packed) + kHeaderBytes;
     const int Mi = static_cast<int>(M), f16 = (y_dtype == PTQTP_F16);
     hipError_t e;
-    if (M == 1 && g_tune_stream != 0) {
+    if (M == 1) {
         LinearDesc d;
         d.records = records; d.x = x; d.y = y;
         d.N = static_cast<int32_t>(s.N); d.K = static_cast<int32_t>(s.K);
         d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
         d.first_item = 0; d.pad = 0;
         e = launch_items<false>(nullptr, d, f16, s.RT, s.KS, stream);
-    } else if (M == 1) {
-        const int W = pick_waves(s.KS, 16);
-        int R = g_tune_rows > 0 ? g_tune_rows : (s.RT >= 4096 ? 2 : 1);
-        if (R >= 4) e = launch_gemv<1, 4, true>(records, x, y, Mi, s, W, f16, stream);
-        else if (R >= 2) e = launch_gemv<1, 2, true>(records, x, y, Mi, s, W, f16, stream);
-        else e = launch_gemv<1, 1, true>(records, x, y, Mi, s, W, f16, stream);
     } else if (M >= 256 || g_tune_tile == 1) {
         // 256-row x 128-token tiles leave CUs idle on small problems: use the 128 x 128 variant then
         const int64_t big_tiles = ((s.RT + 15) / 16) * ((M + 127) / 128);
@@ -1528,21 +1381,9 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
             void *yc = static_cast<char *>(y) + static_cast<size_t>(m0) * s.N * (f16 ? 2 : 4);
             e = launch_small(records, xc, yc, mc, s, f16, stream);
         }
-    } else if (g_tune_small != 0) {
+    } else {
         // many row tiles: two per item share one set of activation operands
         e = launch_small(records, x, y, Mi, s, f16, stream);
-    } else if (M <= 16) {
-        const int W = pick_waves(s.KS, 16);
-        int R = g_tune_rows > 0 ? g_tune_rows : (s.RT >= 4096 ? 2 : 1);
-        if (R >= 4) e = launch_gemv<1, 4, false>(records, x, y, Mi, s, W, f16, stream);
-        else if (R >= 2) e = launch_gemv<1, 2, false>(records, x, y, Mi, s, W, f16, stream);
-        else e = launch_gemv<1, 1, false>(records, x, y, Mi, s, W, f16, stream);
-    } else if (M <= 32) {
-        const int W = pick_waves(s.KS, 8);
-        e = launch_gemv<2, 1, false>(records, x, y, Mi, s, W, f16, stream);
-    } else {
-        const int W = pick_waves(s.KS, 8);
-        e = launch_gemv<4, 1, false>(records, x, y, Mi, s, W, f16, stream);
     }
     return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
@@ -1745,11 +1586,6 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
         g_tune_small_fold = value;
         return PTQTP_OK;
     }
-    if (!strcmp(key, "gemv_stream")) {
-        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
-        g_tune_stream = value;
-        return PTQTP_OK;
-    }
     if (!strcmp(key, "stream_waves")) {
         if (value < 0 || value > 16) return PTQTP_ERR_SHAPE;
         g_tune_stream_waves = value;
@@ -1780,24 +1616,9 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
         g_tune_small_waves = value;
         return PTQTP_OK;
     }
-    if (!strcmp(key, "small_items")) {
-        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
-        g_tune_small = value;
-        return PTQTP_OK;
-    }
     if (!strcmp(key, "stream_depth")) {
         if (value != 0 && value != 1 && value != 2 && value != 4) return PTQTP_ERR_SHAPE;
         g_tune_stream_depth = value;
-        return PTQTP_OK;
-    }
-    if (!strcmp(key, "gemv_waves")) {
-        if (value < 0 || value > 16) return PTQTP_ERR_SHAPE;
-        g_tune_waves = value;
-        return PTQTP_OK;
-    }
-    if (!strcmp(key, "gemv_rows")) {
-        if (value != 0 && value != 1 && value != 2 && value != 4) return PTQTP_ERR_SHAPE;
-        g_tune_rows = value;
         return PTQTP_OK;
     }
     return PTQTP_ERR_SHAPE;

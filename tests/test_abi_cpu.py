@@ -169,9 +169,9 @@ def test_argument_validation_without_launch(lib):
     assert lib.ptqtp_gemv(ctypes.c_void_p(0x10010), fake, fake, 0, 1, N, K, 128, None, 0, None) == 6
     assert lib.ptqtp_gemv(fake, ctypes.c_void_p(0x10002), fake, 0, 1, N, K, 128, None, 0, None) == 6
     # tuning hook
-    assert lib.ptqtp_tune(b"gemv_waves", 8) == 0
-    assert lib.ptqtp_tune(b"gemv_waves", 0) == 0
-    assert lib.ptqtp_tune(b"gemv_rows", 3) == 2
+    assert lib.ptqtp_tune(b"small_waves", 8) == 0
+    assert lib.ptqtp_tune(b"small_waves", 0) == 0
+    assert lib.ptqtp_tune(b"small_rows", 3) == 2
     assert lib.ptqtp_tune(b"stream_depth", 3) == 2
     assert lib.ptqtp_tune(b"stream_waves", 17) == 2
     assert lib.ptqtp_tune(b"stream_waves", 0) == 0

@@ -101,24 +101,6 @@ def test_gemv_shapes(ptq, N, K):
     check(y, lin, x)
 
 
-@pytest.mark.parametrize("waves,rows", [(1, 1), (3, 2), (16, 4), (5, 1), (16, 2)])
-def test_gemv_launch_shapes(ptq, waves, rows):
-    # every launch shape the tuning hook can select computes the same layer
-    lin = workloads.make_linear(200, 2304, 54)
-    x = workloads.make_x(1, 2304, 54)
-    packed = pack(ptq, lin)
-    try:
-        ptq.ptqtp_tune("gemv_waves", waves)
-        ptq.ptqtp_tune("gemv_rows", rows)
-        y = ptq.ptqtp_gemv(packed, dev(x).reshape(-1), 200, 2304)
-        check(y, lin, x)
-        xm = workloads.make_x(9, 2304, 54, 9)
-        check(ptq.ptqtp_gemm_small(packed, dev(xm), 200, 2304), lin, xm)
-    finally:
-        ptq.ptqtp_tune("gemv_waves", 0)
-        ptq.ptqtp_tune("gemv_rows", 0)
-
-
 @pytest.mark.parametrize("waves,depth", [(1, 1), (4, 4), (8, 2), (16, 1), (3, 4), (16, 4)])
 def test_gemv_item_kernel_launch_shapes(ptq, waves, depth):
     # waves per item x records in flight: all give the same layer, including K/256 < waves,
@@ -133,17 +115,6 @@ def test_gemv_item_kernel_launch_shapes(ptq, waves, depth):
     finally:
         ptq.ptqtp_tune("stream_waves", 0)
         ptq.ptqtp_tune("stream_depth", 0)
-
-
-def test_gemv_tiled_kernel_still_right(ptq):
-    try:
-        ptq.ptqtp_tune("gemv_stream", 0)
-        for N, K in [(200, 2304), (7, 640), (1000, 4096)]:
-            lin = workloads.make_linear(N, K, 54, N)
-            x = workloads.make_x(1, K, 54, N)
-            check(ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), N, K), lin, x)
-    finally:
-        ptq.ptqtp_tune("gemv_stream", -1)
 
 
 def test_gemv_batch_matches_oracle_and_single_calls(ptq):
