@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     PTQTP_F16, PTQTP_F32, PTQTP_FUSED_PLANES, PTQTP_GEMM_SMALL_MAX_M, PtqtpError, lib_path,
     BatchPlan, ptqtp_gemm, ptqtp_gemm_batch, ptqtp_gemm_small, ptqtp_gemv, ptqtp_gemv_batch, ptqtp_gemv_batch_plan, ptqtp_pack, ptqtp_quantize, ptqtp_packed_bytes, ptqtp_status_string,
     ptqtp_tune, ptqtp_unpack, ptqtp_version, ptqtp_workspace_bytes,
-    PTQTP_EPI_NONE, PTQTP_EPI_SWIGLU, ChainPlan, ptqtp_chain_plan, ptqtp_chain_run,
+    PTQTP_EPI_NONE, PTQTP_EPI_SWIGLU, ChainPlan, ptqtp_chain_plan, ptqtp_chain_run, ptqtp_chain_run_batch,
 )

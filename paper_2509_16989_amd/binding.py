@@ -62,6 +62,8 @@ def _load():
         lib.ptqtp_chain_plan.argtypes = [p, i32, i32, p, sz, p]
         lib.ptqtp_chain_run.restype = i32
         lib.ptqtp_chain_run.argtypes = [p, i32, i32, p, p]
+        lib.ptqtp_chain_run_batch.restype = i32
+        lib.ptqtp_chain_run_batch.argtypes = [p, i32, i32, i64, p]
         lib.ptqtp_batch_plan_bytes.restype = sz
         lib.ptqtp_batch_plan_bytes.argtypes = [p, i32, i32]
         lib.ptqtp_batch_items.restype = i64
@@ -298,3 +300,10 @@ def ptqtp_chain_run(plan: ChainPlan) -> None:
     st = _load().ptqtp_chain_run(plan.arr, plan.count, plan.group, plan.plan.data_ptr(), _stream())
     if st:
         raise PtqtpError(st, "ptqtp_chain_run")
+
+
+def ptqtp_chain_run_batch(plan: ChainPlan, M: int) -> None:
+    """The chain at M tokens per stage (x [M,K], y / residual [M,n_out]); one launch per stage."""
+    st = _load().ptqtp_chain_run_batch(plan.arr, plan.count, plan.group, int(M), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_chain_run_batch")

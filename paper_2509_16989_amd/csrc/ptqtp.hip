@@ -352,7 +352,7 @@ template <int MT, int R, int S, bool PLAN, int ML>
 __global__ void __launch_bounds__(MT * R >= 8 ? 256 : 512)
 gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict__ records_,
                   const uint16_t *__restrict__ x_, void *__restrict__ y_, int M, int N_, int K_, int RT_, int KS_,
-                  int y_f16_)
+                  int y_f16_, const uint16_t *__restrict__ residual, int gated)
 {
     extern __shared__ float red[];                     // [W][R][MT][16 tokens][16 rows]; first used as bounce slots
     const int lane = threadIdx.x & 63;
@@ -362,7 +362,10 @@ gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict
     const uint8_t *records = records_;
     const uint16_t *x = x_;
     void *y = y_;
-    int N = N_, K = K_, RT = RT_, KS = KS_, y_f16 = y_f16_, rt0 = blockIdx.x * R;
+    // gated (decode chain, R == 2): the item's two row tiles are gate tile i and up tile i of a stacked
+    // [gate; up] linear, RT/2 tiles apart; otherwise R consecutive tiles
+    const int rstride = gated ? RT_ / 2 : 1;
+    int N = N_, K = K_, RT = RT_, KS = KS_, y_f16 = y_f16_, rt0 = gated ? blockIdx.x : blockIdx.x * R;
     if (PLAN) {
         if (static_cast<int>(blockIdx.x) >= plan->total_items) return;   // whole workgroup, before any barrier
         const LinearDesc *table = reinterpret_cast<const LinearDesc *>(plan + 1);
@@ -398,7 +401,7 @@ gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict
             kse = kse >= KS ? kse - KS : kse;              // rotated start: neighbours hit different x lines
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const int rt = rt0 + r < RT ? rt0 + r : rt0;
+                const int rt = rt0 + r * rstride < RT ? rt0 + r * rstride : rt0;
                 const uint8_t *rec = records + (static_cast<size_t>(rt) * KS + kse) * kRecordBytes;
                 p1[i][r] = load_stream<uintx4>(rec + lane * 16);
                 p2[i][r] = load_stream<uintx4>(rec + kPlaneBytes + lane * 16);
@@ -468,14 +471,21 @@ gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict
             for (int j = 0; j < 4; ++j)
                 red[w * OUT + ((r * MT + mt) * 16 + 4 * q + j) * 16 + nl] = yacc[r][mt][j];
     __syncthreads();
-    for (int o = threadIdx.x; o < OUT; o += blockDim.x) {
+    const int n_out = gated ? N / 2 : N;              // gated: silu(gate) * up, one output per (gate, up) row pair
+    for (int o = threadIdx.x; o < (gated ? OUT / R : OUT); o += blockDim.x) {
         float s = 0.f;
         for (int ww = 0; ww < W; ++ww) s += red[ww * OUT + o];
         const int on = o & 15, t = o >> 4;
         const int m = (t / 16 % MT) * 16 + (t & 15), r = t / (16 * MT);
         const int n = (rt0 + r) * kTileRows + on;
-        if (m < M && rt0 + r < RT && n < N) {
-            const size_t off = static_cast<size_t>(m) * N + n;
+        if (m < M && rt0 + r * rstride < RT && n < n_out) {
+            if (gated) {
+                float u = 0.f;
+                for (int ww = 0; ww < W; ++ww) u += red[ww * OUT + o + MT * 256];
+                s = (s / (1.0f + __expf(-s))) * u;
+            }
+            const size_t off = static_cast<size_t>(m) * n_out + n;
+            if (residual != nullptr) s += half_bits_to_float(load_global<uint16_t>(residual + off));
             if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(s);
             else reinterpret_cast<float *>(y)[off] = s;
         }
@@ -1046,7 +1056,8 @@ int g_tune_small_waves = 0, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_smal
 
 template <int MT, int R, int S, bool PLAN, int ML>
 hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
-                                  int N, int K, int RT, int KS, int y_f16, int64_t grid, int W, hipStream_t stream)
+                                  int N, int K, int RT, int KS, int y_f16, int64_t grid, int W, hipStream_t stream,
+                                  const uint16_t *residual = nullptr, int gated = 0)
 {
     size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
     if (lds < static_cast<size_t>(W) * kSlotBytes) lds = static_cast<size_t>(W) * kSlotBytes;
@@ -1058,37 +1069,39 @@ hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records
         configured = true;
     }
     hipLaunchKernelGGL((gemm_items_kernel<MT, R, S, PLAN, ML>), dim3(static_cast<unsigned>(grid)), dim3(W * 64), lds,
-                       stream, plan, records, x, y, M, N, K, RT, KS, y_f16);
+                       stream, plan, records, x, y, M, N, K, RT, KS, y_f16, residual, gated);
     return hipGetLastError();
 }
 
 // load instructions per 16-token tile needed for M tokens
 template <int MT, int R, int S, bool PLAN>
 hipError_t launch_gemm_items_ml(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
-                                int N, int K, int RT, int KS, int y_f16, int64_t grid, int W, hipStream_t stream)
+                                int N, int K, int RT, int KS, int y_f16, int64_t grid, int W, hipStream_t stream,
+                                const uint16_t *residual = nullptr, int gated = 0)
 {
     if constexpr (MT == 1) {
         if (M <= 2)
-            return launch_gemm_items_impl<MT, R, S, PLAN, 1>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream);
+            return launch_gemm_items_impl<MT, R, S, PLAN, 1>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream, residual, gated);
         if (M <= 4)
-            return launch_gemm_items_impl<MT, R, S, PLAN, 2>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream);
+            return launch_gemm_items_impl<MT, R, S, PLAN, 2>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream, residual, gated);
         if (M <= 8)
-            return launch_gemm_items_impl<MT, R, S, PLAN, 4>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream);
+            return launch_gemm_items_impl<MT, R, S, PLAN, 4>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream, residual, gated);
     }
-    return launch_gemm_items_impl<MT, R, S, PLAN, 8>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream);
+    return launch_gemm_items_impl<MT, R, S, PLAN, 8>(plan, records, x, y, M, N, K, RT, KS, y_f16, grid, W, stream, residual, gated);
 }
 
 template <int MT, int R, int S>
 hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
-                             hipStream_t stream)
+                             hipStream_t stream, const uint16_t *residual = nullptr, int gated = 0)
 {
     // measured on 8B shapes: 8 waves per item, except for the register-heavy 64-token x 2-tile case
     int W = g_tune_small_waves > 0 ? g_tune_small_waves : (MT * R >= 8 ? 2 : 8);
     if (W > (MT * R >= 8 ? 4 : 8)) W = MT * R >= 8 ? 4 : 8;
     while (W > 1 && W > s.KS) W /= 2;
-    const int64_t grid = (s.RT + R - 1) / R;
+    const int64_t grid = gated ? s.RT / 2 : (s.RT + R - 1) / R;
     return launch_gemm_items_ml<MT, R, S, false>(nullptr, records, x, y, M, static_cast<int>(s.N), static_cast<int>(s.K),
-                                                 static_cast<int>(s.RT), static_cast<int>(s.KS), y_f16, grid, W, stream);
+                                                 static_cast<int>(s.RT), static_cast<int>(s.KS), y_f16, grid, W, stream,
+                                                 residual, gated);
 }
 
 // batched: every item of a plan, all linears with the same M (2..64)
@@ -1319,20 +1332,40 @@ hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStr
 
 // 2..64 tokens: the small-batch item kernel in the shape that measured best
 hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int f16,
-                        hipStream_t stream)
+                        hipStream_t stream, const uint16_t *residual = nullptr, int gated = 0)
 {
     // measured on 8B shapes: two row tiles per item (sharing one set of activation operands) when the layer has
     // many row tiles, and always for 17..32 tokens; one otherwise
     int R = s.RT >= 512 ? 2 : 1;
     if (M > 16 && M <= 32) R = 2;
     if (g_tune_small_rows > 0) R = g_tune_small_rows;
-    if (M <= 16) return R == 2 ? launch_gemm_items<1, 2, 1>(records, x, y, M, s, f16, stream)
-                               : launch_gemm_items<1, 1, 2>(records, x, y, M, s, f16, stream);
-    if (M <= 32) return R == 2 ? launch_gemm_items<2, 2, 1>(records, x, y, M, s, f16, stream)
-                               : launch_gemm_items<2, 1, 1>(records, x, y, M, s, f16, stream);
-    return R == 2 ? launch_gemm_items<4, 2, 1>(records, x, y, M, s, f16, stream)
-                  : launch_gemm_items<4, 1, 1>(records, x, y, M, s, f16, stream);
+    if (gated) R = 2;                                  // a (gate tile, up tile) pair per item
+    if (M <= 16) return R == 2 ? launch_gemm_items<1, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
+                               : launch_gemm_items<1, 1, 2>(records, x, y, M, s, f16, stream, residual, gated);
+    if (M <= 32) return R == 2 ? launch_gemm_items<2, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
+                               : launch_gemm_items<2, 1, 1>(records, x, y, M, s, f16, stream, residual, gated);
+    return R == 2 ? launch_gemm_items<4, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
+                  : launch_gemm_items<4, 1, 1>(records, x, y, M, s, f16, stream, residual, gated);
 }
+
+}  // namespace
+
+// one stage of a decode chain at 1..64 tokens (called from ptqtp_chain.hip): the small-batch item kernel with the
+// stage's epilogue in its final reduction
+namespace ptqtp_detail {
+hipError_t small_batch_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M,
+                             int64_t N, int64_t K, int y_f16, int gated, hipStream_t stream)
+{
+    Shape s;
+    s.N = N; s.K = K; s.NG = K / 128;
+    s.RT = (N + kTileRows - 1) / kTileRows;
+    s.KS = (K + kStepK - 1) / kStepK;
+    return launch_small(records, x, y, M, s, y_f16, stream, residual, gated);
+}
+}
+
+namespace {
+
 
 ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M,
                          int64_t N, int64_t K, int32_t group, void *stream_, int64_t max_m, bool fuse_planes = false)

@@ -14,6 +14,12 @@
 #include "ptqtp.h"
 #include "ptqtp_device.hpp"
 
+namespace ptqtp_detail {
+// ptqtp.hip: the small-batch item kernel with a stage's epilogue in its final reduction
+hipError_t small_batch_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M,
+                             int64_t N, int64_t K, int y_f16, int gated, hipStream_t stream);
+}
+
 namespace {
 
 constexpr int kChainMaxWaves = 16;
@@ -289,6 +295,21 @@ ptqtp_status ptqtp_chain_run(const ptqtp_stage *stages, int32_t count, int32_t g
         else hipLaunchKernelGGL((chain_items_kernel<1>), grid, block, 0, stream, ph, lr[l].first_item);
     }
     return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
+ptqtp_status ptqtp_chain_run_batch(const ptqtp_stage *stages, int32_t count, int32_t group, int64_t M, void *stream_) {
+    int n_levels; int64_t total; ptqtp_status st;
+    if (!chain_geometry(stages, count, group, nullptr, nullptr, &n_levels, &total, &st)) return st;
+    if (M < 1 || M > PTQTP_GEMM_SMALL_MAX_M) return PTQTP_ERR_SHAPE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    for (int i = 0; i < count; ++i) {
+        const ptqtp_stage &s = stages[i];
+        const hipError_t e = ptqtp_detail::small_batch_stage(
+            static_cast<const uint8_t *>(s.packed) + kHeaderBytes, s.x, s.y, s.residual, static_cast<int>(M), s.N, s.K,
+            s.y_dtype == PTQTP_F16, s.epilogue == PTQTP_EPI_SWIGLU, stream);
+        if (e != hipSuccess) return PTQTP_ERR_HIP;
+    }
+    return PTQTP_OK;
 }
 
 }  // extern "C"

@@ -31,7 +31,7 @@ def test_header_symbols_exported(lib):
             "ptqtp_workspace_bytes", "ptqtp_status_string", "ptqtp_version", "ptqtp_tune", "ptqtp_gemm",
             "ptqtp_gemv_batch", "ptqtp_gemv_batch_plan", "ptqtp_batch_items", "ptqtp_batch_plan_bytes",
             "ptqtp_quantize", "ptqtp_quantize_workspace_bytes", "ptqtp_gemm_batch", "ptqtp_chain_plan_bytes",
-            "ptqtp_chain_plan", "ptqtp_chain_run"} <= set(names)
+            "ptqtp_chain_plan", "ptqtp_chain_run", "ptqtp_chain_run_batch"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in ptqtp.h but not exported"
 
@@ -116,8 +116,12 @@ def test_chain_plan_validation(lib):
     arr = stages()
     assert lib.ptqtp_chain_run(arr, 3, 128, None, None) == 1
     assert lib.ptqtp_chain_run(arr, 3, 128, ctypes.c_void_p(0x100010), None) == 6
+    assert lib.ptqtp_chain_run_batch(arr, 3, 128, 0, None) == 2
+    assert lib.ptqtp_chain_run_batch(arr, 3, 128, 65, None) == 2
+    assert lib.ptqtp_chain_run_batch(None, 3, 128, 4, None) == 1
     arr[1].N = 944
     assert lib.ptqtp_chain_run(arr, 3, 128, fake, None) == 2
+    assert lib.ptqtp_chain_run_batch(arr, 3, 128, 4, None) == 2
 
 
 def test_quantize_validation(lib):

@@ -35,9 +35,13 @@ def pack(ptq, lin):
 
 
 def check_stage(out_gpu, lin, x16, epilogue, residual16):
-    """out_gpu: tensor [n_out]; x16 / residual16: numpy float16 as the GPU saw them."""
-    st = oracle.stage(lin, x16[None, :], epilogue, residual=None if residual16 is None else residual16[None, :], threads=8)
-    ref, E, E2 = st["out"][0], st["err"][0], st["err2"][0]
+    """out_gpu: tensor [n_out] or [M, n_out]; x16 / residual16: numpy float16 as the GPU saw them."""
+    if x16.ndim == 1:
+        x16 = x16[None, :]
+        residual16 = None if residual16 is None else residual16[None, :]
+        out_gpu = out_gpu[None, :]
+    st = oracle.stage(lin, x16, epilogue, residual=residual16, threads=8)
+    ref, E, E2 = st["out"], st["err"], st["err2"]
     got = out_gpu.detach().cpu().numpy().astype(np.float64)
     assert got.shape == ref.shape and np.all(np.isfinite(got))
     rounding = HALF_ULP * np.abs(ref) + 1e-7 if out_gpu.dtype == torch.float16 else 2.0 ** -23 * np.abs(ref)
@@ -157,3 +161,66 @@ def test_chain_independent_stages_share_a_level(ptq):
     for p, y in zip(parts, outs):
         check_stage(y, p, x, "none", None)
     check_stage(yo, o, outs[0].cpu().numpy(), "none", x)
+
+
+# ---------------------------------------------------------------- the chain at several tokens per stage
+@pytest.mark.parametrize("M", [1, 3, 16, 24, 40, 64])
+@pytest.mark.parametrize("N,K,epi,res,ydt", [
+    (200, 640, "none", True, torch.float16), (1024, 1024, "none", False, torch.float32),
+    (960, 384, "swiglu", False, torch.float16), (2048, 1024, "swiglu", True, torch.float32), (64, 128, "swiglu", True, torch.float16),
+])
+def test_chain_batch_single_stage(ptq, M, N, K, epi, res, ydt):
+    lin = workloads.make_linear(N, K, 85, N, K)
+    x = workloads.make_x(M, K, 85, N, M)
+    n_out = N // 2 if epi == "swiglu" else N
+    r = workloads.make_x(M, n_out, 85, N, M, 7) if res else None
+    y = torch.full((M, n_out), float("nan"), dtype=ydt, device="cuda:0")
+    plan = ptq.ptqtp_chain_plan([dict(packed=pack(ptq, lin), x=dev(x), y=y, N=N, K=K, level=0,
+                                      residual=dev(r) if res else None,
+                                      epilogue=ptq.PTQTP_EPI_SWIGLU if epi == "swiglu" else ptq.PTQTP_EPI_NONE)])
+    ptq.ptqtp_chain_run_batch(plan, M)
+    torch.cuda.synchronize()
+    check_stage(y, lin, x, epi, r)
+
+
+def build_stack_batch(ptq, layers, H, KV, I, M, seed):
+    lins, stages, bufs = [], [], {}
+    z = lambda n: torch.zeros((M, n), dtype=torch.float16, device="cuda:0")
+    bufs["x0"] = z(H)
+    cur, level = bufs["x0"], 0
+    for l in range(layers):
+        # o reads a buffer of its own that the test fills from qkv's output (the q part of every token)
+        qkv = workloads.make_linear(H + 2 * KV, H, seed, l, 1)
+        o = workloads.make_linear(H, H, seed, l, 2)
+        gu = workloads.make_linear(2 * I, H, seed, l, 3)
+        dn = workloads.make_linear(H, I, seed, l, 4)
+        t_qkv, t_q, t_attn, t_h, t_out = z(H + 2 * KV), z(H), z(H), z(I), z(H)
+        for lin, xin, yout, res, epi in [(qkv, cur, t_qkv, None, "none"), (o, t_q, t_attn, cur, "none"),
+                                         (gu, t_attn, t_h, None, "swiglu"), (dn, t_h, t_out, t_attn, "none")]:
+            stages.append(dict(packed=pack(ptq, lin), x=xin, y=yout, N=lin["N"], K=lin["K"], level=level, residual=res,
+                               epilogue=ptq.PTQTP_EPI_SWIGLU if epi == "swiglu" else ptq.PTQTP_EPI_NONE))
+            lins.append((lin, xin, yout, res, epi))
+            level += 1
+        bufs[("q", l)] = (t_qkv, t_q)
+        cur = t_out
+    return lins, stages, bufs
+
+
+@pytest.mark.parametrize("M", [5, 33])
+def test_chain_batch_dependent_stack(ptq, M):
+    # with M tokens a row of qkv's output is not contiguous with the next token's q part, so o gets its input through
+    # a copy the test makes between two runs of sub-chains (stands in for attention); every stage is checked on its real input
+    H, KV, I, layers = 256, 128, 384, 2
+    lins, stages, bufs = build_stack_batch(ptq, layers, H, KV, I, M, 86)
+    bufs["x0"].copy_(dev(workloads.make_x(M, H, 86, M)))
+    for l in range(layers):
+        first = ptq.ptqtp_chain_plan(stages[4 * l: 4 * l + 1])
+        rest = ptq.ptqtp_chain_plan(stages[4 * l + 1: 4 * l + 4])
+        ptq.ptqtp_chain_run_batch(first, M)
+        t_qkv, t_q = bufs[("q", l)]
+        t_q.copy_(t_qkv[:, :H])
+        ptq.ptqtp_chain_run_batch(rest, M)
+    torch.cuda.synchronize()
+    for lin, xin, yout, res, epi in lins:
+        check_stage(yout, lin, xin.cpu().numpy(), epi, None if res is None else res.cpu().numpy())
+    assert not torch.equal(lins[-1][2], lins[-1][3])
