@@ -166,6 +166,15 @@ def test_argument_validation_without_launch(lib):
     assert lib.ptqtp_gemv(fake, fake, fake, 0, 1, N, 200, 128, None, 0, None) == 2    # K % group
     assert lib.ptqtp_gemm_small(fake, fake, fake, 0, 65, N, K, 128, None, 0, None) == 2
     assert lib.ptqtp_gemm_small(fake, fake, fake, 0, 0, N, K, 128, None, 0, None) == 2
+    # empty layers and the largest batch
+    assert lib.ptqtp_gemv(fake, fake, fake, 0, 1, 0, K, 128, None, 0, None) == 2
+    assert lib.ptqtp_gemv(fake, fake, fake, 0, 1, N, 0, 128, None, 0, None) == 2
+    assert lib.ptqtp_gemm(fake, fake, fake, 0, 65537, N, K, 128, None, 0, None) == 2
+    assert lib.ptqtp_packed_bytes(1, 0, K, 128) == 0 and lib.ptqtp_packed_bytes(1, N, 0, 128) == 0
+    # the fused-planes flag belongs to ptqtp_gemm only
+    assert lib.ptqtp_gemv(fake, fake, fake, 16, 1, N, K, 128, None, 0, None) == 5
+    assert lib.ptqtp_gemm_small(fake, fake, fake, 16 | 1, 4, N, K, 128, None, 0, None) == 5
+    assert lib.ptqtp_gemm(fake, fake, fake, 16 | 2, 300, N, K, 128, None, 0, None) == 5
     # group, dtype, size, alignment
     assert lib.ptqtp_gemv(fake, fake, fake, 0, 1, N, K, 64, None, 0, None) == 3
     assert lib.ptqtp_gemv(fake, fake, fake, 7, 1, N, K, 128, None, 0, None) == 5
