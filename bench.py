@@ -4,11 +4,13 @@
 A step is one decode step through the linear layers of an 8B-shaped decoder
 stack at batch 1: `--layers` (default 32) layers x the seven linears q, k, v,
 o, gate, up, down, every linear with its own packed blob and its own x, run
-back to back on one stream.  The shapes are BASELINE config 1; walking 32
+back to back on one stream.  The shapes are those of an 8B LLaMA-3 decoder; walking 32
 distinct layer copies (3.7 GB of packed planes + scales) keeps every launch
 cold in HBM instead of warm in the 256 MB Infinity Cache.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (GB/s of algorithmic bytes), ms_per_step, the roofline of the
+dominant kernel (measured with HIP events on the launch stream) and the fp64 CPU oracle timed beside it;
+`--per-shape` adds small-batch, dependent-chain, 70B, prefill and quantizer figures under "per_shape".
 """
 from __future__ import annotations
 
@@ -250,9 +252,10 @@ def _graph_time(torch, stream, run, launches, reps=10):
 
 
 def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False, quick=False):
-    """The other BASELINE configs, one linear per launch (not the headline):
-    config 1/2: each 8B shape at M = 1, 4, 16, 64, cold (walking the 32 layer copies) -- and M = 1 hot;
-    config 4:   70B shapes at M = 1 and 32 (hot: one copy) and prefill M = 2048 on the MFMA tile;
+    """The workloads beside the headline, one linear per launch:
+    each 8B shape at M = 1, 4, 16, 64, cold (walking the 32 layer copies) -- and M = 1 hot;
+    70B shapes at M = 1 and 32 (hot: one copy) and prefill M = 2048 on the MFMA tiles;
+    the whole stack in one launch at M = 4, 16, 64; the dependent decode chain;
     plus the quantizer (ptqtp_quantize) on two 8B shapes, with the oracle quantizer timed on a 256 x 4096 sample."""
     import workloads
     res = {"8b": {}, "70b": {}}
