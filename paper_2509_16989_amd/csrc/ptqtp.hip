@@ -31,6 +31,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
+#include <type_traits>
 
 #include "ptqtp.h"
 #include "ptqtp_device.hpp"
@@ -227,6 +228,7 @@ gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int si
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int W = blockDim.x >> 6;
     const int nl = lane & 15, q = lane >> 4;
+    const uint32_t lane16 = lane * 16u, nl8 = nl * 8u;
     const int item = blockIdx.x;
 
     const LinearDesc *dp = &single;
@@ -251,47 +253,55 @@ gemv_items_kernel(const PlanHeader *__restrict__ plan, LinearDesc single, int si
     const char *xs_rd = reinterpret_cast<const char *>(&xs[w][0]) + q * 16;
     float yacc = 0.f;
 
-    for (int ks0 = w; ks0 < KS; ks0 += S * W) {
-        StepRegs r[S];
-        // issue: S steps in flight.  Steps past the end re-read the wave's first step (address
-        // stays valid, result unused) so that the number of outstanding loads is static.
-#pragma unroll
-        for (int i = 0; i < S; ++i) {
-            const int ks = ks0 + i * W;
-            int kse = (ks < KS ? ks : ks0) + rot;       // rotated start: neighbours hit different x lines
-            kse = kse >= KS ? kse - KS : kse;
-            const uint8_t *rec = rec0 + static_cast<size_t>(kse) * kRecordBytes;
-            r[i].p1 = load_stream<uintx4>(rec + lane * 16);
-            r[i].p2 = load_stream<uintx4>(rec + kPlaneBytes + lane * 16);
-            r[i].sc = load_stream<uintx2>(rec + 2 * kPlaneBytes + nl * 8);
-            int k = kse * kStepK + lane * 4;
-            k = k < K ? k : 0;                                   // odd number of groups: tail lanes
-            r[i].xr = load_global<uintx2>(x + k);
-        }
-#pragma unroll
-        for (int i = 0; i < S; ++i) {
-            const int ks = ks0 + i * W;
-            if (ks < KS) {
-                uintx2 xr = r[i].xr;
-                int kr = ks + rot;
-                kr = kr >= KS ? kr - KS : kr;
-                if (kr * kStepK + lane * 4 >= K) xr = uintx2{0, 0};
-                xs[w][lane] = xr;                                // wave-private bounce: no barrier
-                if (nl == 0) {
-#pragma unroll
-                    for (int f = 0; f < 8; ++f)
-                        xa[0][f] = *reinterpret_cast<const uintx4 *>(xs_rd + (f >> 2) * 256 + (f & 3) * 64);
+    // tail: K is an odd number of 128-column groups, so the last record is half padding and the lanes of its second
+    // half must not read x past its end.  The choice is made once per item, outside the loop (every LLaMA shape
+    // takes the branch without the checks), so that each loop stays straight-line code.
+    auto run = [&](auto tail_tag) {
+        constexpr bool tail = decltype(tail_tag)::value;
+        for (int ks0 = w; ks0 < KS; ks0 += S * W) {
+            StepRegs r[S];
+            // issue: S steps in flight.  Steps past the end re-read the wave's first step (address
+            // stays valid, result unused) so that the number of outstanding loads is static.
+    #pragma unroll
+            for (int i = 0; i < S; ++i) {
+                const int ks = ks0 + i * W;
+                int kse = (ks < KS ? ks : ks0) + rot;       // rotated start: neighbours hit different x lines
+                kse = kse >= KS ? kse - KS : kse;
+                const uint8_t *rec = rec0 + static_cast<size_t>(kse) * kRecordBytes;
+                // uniform base + 32-bit lane offset: the loads take the record address from scalar registers
+                r[i].p1 = load_stream<uintx4>(rec + lane16);
+                r[i].p2 = load_stream<uintx4>(rec + (kPlaneBytes + lane16));
+                r[i].sc = load_stream<uintx2>(rec + (2 * kPlaneBytes + nl8));
+                int k = kse * kStepK + lane * 4;
+                if (tail) k = k < K ? k : 0;                         // odd number of groups: tail lanes
+                r[i].xr = load_global<uintx2>(x + static_cast<uint32_t>(k));
+            }
+    #pragma unroll
+            for (int i = 0; i < S; ++i) {
+                const int ks = ks0 + i * W;
+                if (ks < KS) {
+                    uintx2 xr = r[i].xr;
+                    int kr = ks + rot;
+                    kr = kr >= KS ? kr - KS : kr;
+                    if (tail && kr * kStepK + lane * 4 >= K) xr = uintx2{0, 0};
+                    xs[w][lane] = xr;                                // wave-private bounce: no barrier
+                    if (nl == 0) {
+    #pragma unroll
+                        for (int f = 0; f < 8; ++f)
+                            xa[0][f] = *reinterpret_cast<const uintx4 *>(xs_rd + (f >> 2) * 256 + (f & 3) * 64);
+                    }
+                    const float a1g0 = half_bits_to_float(r[i].sc.x & 0xffffu), a1g1 = half_bits_to_float(r[i].sc.x >> 16);
+                    const float a2g0 = half_bits_to_float(r[i].sc.y & 0xffffu), a2g1 = half_bits_to_float(r[i].sc.y >> 16);
+                    floatx4 acc[1];
+                    group_sum<1, 0>(xa, r[i].p1, acc); yacc = fmaf(a1g0, acc[0][0], yacc);
+                    group_sum<1, 1>(xa, r[i].p1, acc); yacc = fmaf(a1g1, acc[0][0], yacc);
+                    group_sum<1, 0>(xa, r[i].p2, acc); yacc = fmaf(a2g0, acc[0][0], yacc);
+                    group_sum<1, 1>(xa, r[i].p2, acc); yacc = fmaf(a2g1, acc[0][0], yacc);
                 }
-                const float a1g0 = half_bits_to_float(r[i].sc.x & 0xffffu), a1g1 = half_bits_to_float(r[i].sc.x >> 16);
-                const float a2g0 = half_bits_to_float(r[i].sc.y & 0xffffu), a2g1 = half_bits_to_float(r[i].sc.y >> 16);
-                floatx4 acc[1];
-                group_sum<1, 0>(xa, r[i].p1, acc); yacc = fmaf(a1g0, acc[0][0], yacc);
-                group_sum<1, 1>(xa, r[i].p1, acc); yacc = fmaf(a1g1, acc[0][0], yacc);
-                group_sum<1, 0>(xa, r[i].p2, acc); yacc = fmaf(a2g0, acc[0][0], yacc);
-                group_sum<1, 1>(xa, r[i].p2, acc); yacc = fmaf(a2g1, acc[0][0], yacc);
             }
         }
-    }
+    };
+    if (K & (kStepK - 1)) run(std::true_type{}); else run(std::false_type{});
 
     if (q == 0) red[w][nl] = yacc;
     __syncthreads();
