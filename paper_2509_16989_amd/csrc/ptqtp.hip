@@ -539,7 +539,7 @@ struct TileRecs {               // the records of a wave's four row tiles for on
 template <int MTW, bool FUSE>
 __global__ void __launch_bounds__(256)
 gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
-                 int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB)
+                 int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB, int nb0)
 {
     extern __shared__ char xt[];                     // [2][TM][kTileXStride]
     constexpr int TM = 16 * MTW, NRT = 16;           // tokens, row tiles per workgroup
@@ -548,7 +548,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nl = lane & 15, q = lane >> 4;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int nb = (slot / MB) * 8 + xcd, mb = slot % MB;
+    const int nb = nb0 + (slot / MB) * 8 + xcd, mb = slot % MB;   // this launch covers row blocks nb0 .. NB-1
     if (nb >= NB) return;                            // whole workgroup, before any barrier
     const int m0 = mb * TM;
     const int rt_base = nb * NRT + w * 4;
@@ -865,7 +865,7 @@ constexpr int kTile3BufBytes = 64 * kTile3Chunk;              // one 128-column 
 template <bool FUSE>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
-                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB)
+                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB, int nb0)
 {
     extern __shared__ char xt[];                     // [2][64 chunks][1040]
     constexpr int TM = kTile3Tokens, NRT = 16;
@@ -874,7 +874,7 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
     const int nl = lane & 15, q = lane >> 4;
     const int wm = w & 1, wn = w >> 1;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int nb = (slot / MB) * 8 + xcd, mb = slot % MB;
+    const int nb = nb0 + (slot / MB) * 8 + xcd, mb = slot % MB;   // this launch covers row blocks nb0 .. NB-1
     if (nb >= NB) return;                            // whole workgroup, before any barrier
     const int m0 = mb * TM;
     const int rt_base = nb * NRT + wn * 4;
@@ -1000,11 +1000,11 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
 
 template <bool FUSE>
 hipError_t launch_gemm_tile3(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
-                             hipStream_t stream)
+                             hipStream_t stream, int nb0 = 0, int nb1 = -1)
 {
     const int MB = (M + kTile3Tokens - 1) / kTile3Tokens;
-    const int NB = static_cast<int>((s.RT + 15) / 16);
-    const int64_t grid = static_cast<int64_t>((NB + 7) / 8) * 8 * MB;
+    const int NB = nb1 >= 0 ? nb1 : static_cast<int>((s.RT + 15) / 16);
+    const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
     const size_t lds = 2 * static_cast<size_t>(kTile3BufBytes);
     static bool configured = false;                  // raise the dynamic LDS limit once per process
     if (!configured) {
@@ -1015,7 +1015,7 @@ hipError_t launch_gemm_tile3(const uint8_t *records, const uint16_t *x, void *y,
     }
     hipLaunchKernelGGL((gemm_tile3_kernel<FUSE>), dim3(static_cast<unsigned>(grid)), dim3(512), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
-                       static_cast<int>(s.KS), y_f16, MB, NB);
+                       static_cast<int>(s.KS), y_f16, MB, NB, nb0);
     return hipGetLastError();
 }
 
@@ -1040,14 +1040,15 @@ hipError_t launch_gemm_tile2(const uint8_t *records, const uint16_t *x, void *y,
     return hipGetLastError();
 }
 
+// row blocks (of 256 rows) nb0 .. nb1-1; nb1 < 0: to the end
 template <int MTW, bool FUSE>
 hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
-                            hipStream_t stream)
+                            hipStream_t stream, int nb0 = 0, int nb1 = -1)
 {
     constexpr int TM = 16 * MTW, NRT = 16;
     const int MB = (M + TM - 1) / TM;
-    const int NB = static_cast<int>((s.RT + NRT - 1) / NRT);
-    const int64_t grid = static_cast<int64_t>((NB + 7) / 8) * 8 * MB;
+    const int NB = nb1 >= 0 ? nb1 : static_cast<int>((s.RT + NRT - 1) / NRT);
+    const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
     const size_t lds = 2 * static_cast<size_t>(TM) * kTileXStride;
     static bool configured = false;                  // raise the dynamic LDS limit once per process
     if (!configured) {
@@ -1058,7 +1059,7 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     }
     hipLaunchKernelGGL((gemm_tile_kernel<MTW, FUSE>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
-                       static_cast<int>(s.KS), y_f16, MB, NB);
+                       static_cast<int>(s.KS), y_f16, MB, NB, nb0);
     return hipGetLastError();
 }
 
@@ -1406,7 +1407,19 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
         const int64_t t3 = ((s.RT + 15) / 16) * ((M + 255) / 256);
         const double eff3 = 1.15 * static_cast<double>(t3) / static_cast<double>((t3 + 255) / 256 * 256);
         const double eff1 = static_cast<double>(big_tiles) / static_cast<double>((big_tiles + 255) / 256 * 256);
-        if (g_tune_tile_variant == 3 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && M >= 256 && eff3 >= eff1))
+        // A last round of 256 x 256 tiles that would leave most CUs idle goes to 256 x 128 tiles instead: the first
+        // nb3 row blocks (whole rounds of 256 x 256 tiles) in one launch, the remaining row blocks in a second one
+        const int NB16 = static_cast<int>((s.RT + 15) / 16), MB3 = static_cast<int>((M + 255) / 256);
+        const int64_t whole = t3 / 256 * 256;
+        const int nb3 = static_cast<int>(whole / MB3);
+        if (g_tune_tile_variant == 0 && g_tune_tile != 1 && M >= 256 && whole > 0 && t3 - whole > 0 &&
+            t3 - whole <= 160 && nb3 > 0 && nb3 < NB16) {
+            e = fuse_planes ? launch_gemm_tile3<true>(records, x, y, Mi, s, f16, stream, 0, nb3)
+                            : launch_gemm_tile3<false>(records, x, y, Mi, s, f16, stream, 0, nb3);
+            if (e == hipSuccess)
+                e = fuse_planes ? launch_gemm_tile<8, true>(records, x, y, Mi, s, f16, stream, nb3)
+                                : launch_gemm_tile<8, false>(records, x, y, Mi, s, f16, stream, nb3);
+        } else if (g_tune_tile_variant == 3 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && M >= 256 && eff3 >= eff1))
             e = fuse_planes ? launch_gemm_tile3<true>(records, x, y, Mi, s, f16, stream)
                             : launch_gemm_tile3<false>(records, x, y, Mi, s, f16, stream);
         else if (!fuse_planes && (g_tune_tile_variant == 2 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && big_tiles < 256)))

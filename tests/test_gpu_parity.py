@@ -451,6 +451,27 @@ def test_gemm_tile_prefill_70b_sampled(ptq, name, flag):
         assert np.all(err <= 3e-5 * B), f"{(err / B).max():.3e}"
 
 
+@pytest.mark.parametrize("flag", [0, 16])
+def test_gemm_prefill_split_between_tile_sizes(ptq, flag):
+    # 36 row blocks x 8 token blocks = 288 tiles of 256 x 256: the first 256 go to that tile, the last four row blocks
+    # (rows 8192..9215) to 256 x 128 tiles in a second launch; rows on both sides of the seam are checked
+    N, K, M = 9216, 256, 2048
+    lin = workloads.make_linear(N, K, 77, 1)
+    x = workloads.make_x(M, K, 77, 2)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=flag, out=y)
+    assert bool(torch.isfinite(y).all())
+    rows = np.unique(np.concatenate([[0, 255, 256, 8191, 8192, 8447, 8448, N - 1], np.random.default_rng(8).integers(0, N, 64)]))
+    toks = np.unique(np.concatenate([[0, 127, 128, 255, 256, 2047], np.random.default_rng(9).integers(0, M, 32)]))
+    sub = (lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows])
+    got = y.cpu().numpy().astype(np.float64)[np.ix_(toks, rows)]
+    if flag:
+        ref, B = oracle.forward_fused(*sub, x[toks])
+    else:
+        ref, B = oracle.forward(*sub, x[toks], threads=8)
+    assert np.all(np.abs(got - ref) <= TIGHT * B), f"{(np.abs(got - ref) / B).max():.3e}"
+
+
 def test_gemm_small_rows_match_gemv(ptq):
     # each token of a batch gets the bits batch-1 would give it? not required (different
     # reduction trees are both correct) -- but both must sit inside the tight gate
