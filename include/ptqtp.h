@@ -266,7 +266,8 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
  * the launch shape the compute calls pick.  key = "stream_waves" (batch 1: waves per item, 1..16),
  * "stream_depth" (batch 1: records in flight per wave: 1, 2 or 4), "small_waves" (one linear at batch > 1:
  * waves per item, 1..8), "small_rows" (row tiles per item / per wave of the small-batch kernels, 1 or 2),
- * "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation loads, -1/1 = shared activation tile),
+ * "chain_waves" (ptqtp_chain_run: waves per item, an even number up to 16), "chain_depth" (ptqtp_chain_run:
+ * records in flight per wave: 1, 2 or 4), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation loads, -1/1 = shared activation tile),
  * "small_fold" (ptqtp_gemm_batch with two row tiles per wave: 1 = multiply the group scales into the
  * expanded trits before the matrix pipe, 0 = rescale the per-group sums after it, -1 = default: before for
  * more than 16 tokens), "tile" (1 = use an MFMA tile for every batch > 1, -1 = default), "tile_variant"

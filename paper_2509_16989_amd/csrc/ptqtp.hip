@@ -36,6 +36,10 @@
 #include "ptqtp.h"
 #include "ptqtp_device.hpp"
 
+namespace ptqtp_detail {
+extern int g_chain_waves, g_chain_depth;       // ptqtp_chain.hip
+}
+
 namespace {
 
 struct BlobHeader {
@@ -1637,6 +1641,16 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
 
 ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!key) return PTQTP_ERR_NULL;
+    if (!strcmp(key, "chain_waves")) {
+        if (value < 0 || value > 16 || (value & 1)) return PTQTP_ERR_SHAPE;
+        ptqtp_detail::g_chain_waves = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "chain_depth")) {
+        if (value != 0 && value != 1 && value != 2 && value != 4) return PTQTP_ERR_SHAPE;
+        ptqtp_detail::g_chain_depth = value;
+        return PTQTP_OK;
+    }
     if (!strcmp(key, "small_fold")) {
         if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
         g_tune_small_fold = value;
