@@ -185,6 +185,38 @@ def test_gemm_batch_matches_oracle(ptq, M):
             check(ent[2], lin, x)
 
 
+def test_batch_plans_replay_from_a_graph(ptq):
+    # a captured batched launch replayed with new activations, eager launches in between: same bits as eager
+    shapes = [(200, 2304), (1024, 1024), (33, 640)]
+    lins = [workloads.make_linear(N, K, 67, i) for i, (N, K) in enumerate(shapes)]
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for M in (1, 12):
+            xs = [torch.zeros((M, K), dtype=torch.float16, device="cuda:0") for (N, K) in shapes]
+            ys = [torch.zeros((M, N), dtype=torch.float32, device="cuda:0") for (N, K) in shapes]
+            plan = ptq.ptqtp_gemv_batch_plan([(pack(ptq, lin), x, y, N, K) for lin, x, y, (N, K) in zip(lins, xs, ys, shapes)])
+            run = (lambda: ptq.ptqtp_gemv_batch(plan)) if M == 1 else (lambda: ptq.ptqtp_gemm_batch(plan, M))
+            run()
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                run()
+            for rep in range(3):
+                xn = [workloads.make_x(M, K, 67, rep, i) for i, (N, K) in enumerate(shapes)]
+                for x, v in zip(xs, xn):
+                    x.copy_(dev(v))
+                for y in ys:
+                    y.fill_(float("nan"))
+                g.replay()
+                stream.synchronize()
+                replayed = [y.clone() for y in ys]
+                run()
+                stream.synchronize()
+                for a, y, lin, v in zip(replayed, ys, lins, xn):
+                    assert torch.equal(a, y)
+                    check(y, lin, v)
+
+
 def test_gemv_unit_vectors_exact(ptq):
     # x = e_j returns column j of W^ = a1 T1 + a2 T2; with a2/a1 in [0.1, 0.5] the sum is exact in fp32
     N, K = 80, 768
