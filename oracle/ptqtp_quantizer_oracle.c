@@ -28,6 +28,16 @@
  * same binary64 operations in the same order, so both sides reach the same bits.  The only long
  * sums, b = S'w, are accumulated exactly in 64-bit integers (w is binary16: w * 2^24 is an
  * integer below 2^40) and converted once.  The convergence norm is accumulated in index order.
+ *
+ * Pins (tests/, -m "not gpu"): zero iterations return the initialisation; the first solve against
+ * its closed form (identical planes: alpha1 = alpha2 = sum|w| / (2G + lambda), lambda raised once before
+ * the solve); alpha against an independent solution of the ridge normal equations at every iteration;
+ * every trit pair against brute force over the nine candidates; the tie order on exact ties; the
+ * error never increasing in the trit step (the monotonicity the paper states); exactly ternary rows
+ * recovered; exact invariance under power-of-two scaling; equivariance under permutations inside a
+ * group; independence of units with a global stopping rule; the binary16 rounding against numpy's
+ * on every finite value and every exact tie.  What the paper leaves open (the order of the lambda
+ * update, the order of ties, which of the two stopping rules) is a reading, not a pin.
  */
 #include <math.h>
 #include <stddef.h>
