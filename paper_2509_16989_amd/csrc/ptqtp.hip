@@ -1132,8 +1132,8 @@ hipError_t launch_gemm_items_plan(const PlanHeader *plan, int64_t items, int M, 
 // small-batch kernel for batched launches: workgroup = four row tiles sharing one activation tile
 // ------------------------------------------------------------------------------------------
 // Wave w owns row tile 4*group + w over the whole K; per 256-column step the workgroup loads the
-// step's activations once (MT*16 tokens x 512 B, coalesced, into a double-buffered LDS tile with
-// padded rows; one barrier per step) and every wave reads its MFMA A operands from there, so the
+// step's activations once (MT*16 tokens x 512 B into a double-buffered LDS tile; one barrier per
+// step) and every wave reads its MFMA A operands from there, so the
 // activation traffic through L1 is a quarter of the per-wave scheme and no cross-wave reduction
 // is needed: each wave stores its own 16 rows.  Needs four row tiles of the same linear per
 // workgroup (eight when a wave owns two), which batch plans guarantee (items are padded to a
@@ -1146,13 +1146,25 @@ hipError_t launch_gemm_items_plan(const PlanHeader *plan, int64_t items, int M, 
 // several token tiles (MT >= 2).
 // At least two waves per SIMD (at most 256 registers per lane) wherever the accumulators allow:
 // the compiler then keeps MFMA results in ordinary VGPRs and the rescale reads them in place.
+// The activation tile goes from global memory straight into LDS (global_load_lds_dwordx4: no staging
+// registers, no address arithmetic per row).  One instruction moves a 1-KiB chunk = the 512 bytes (one 256-column
+// step) of TWO tokens, lane t*32+p bringing 16-byte piece p of token t.  Chunk c of a 32-token block holds tokens c
+// and c+16 and starts at c*1040 bytes, so the 16 tokens of an MFMA token tile sit in 16 chunks skewed by 16 bytes
+// each and the operand read stays one conflict-free ds_read_b128.
+// (With 16 tokens or fewer a chunk holds one token and 528 bytes suffice.)
+template <int MT>
+constexpr int kRowsChunk = MT == 1 ? 528 : 1040;
+template <int MT>
+__device__ __forceinline__ constexpr int rows_operand_offset(int mt, int f) {
+    return (mt >> 1) * (16 * kRowsChunk<MT>) + (mt & 1) * 512 + f * 64;
+}
+
 template <int MT, int RTW, bool FOLD>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((!FOLD && MT * RTW >= 8) ? 1 : 2)))
 gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
 {
-    extern __shared__ char xtile[];                  // [2][MT*16][528]
-    constexpr int XL = 2 * MT;                       // 16-byte loads per thread per step (8 token rows per round)
-    constexpr int kBuf = MT * 16 * 528;
+    extern __shared__ char xtile[];                  // [2][(MT+1)/2 blocks of 32 tokens][16 chunks]
+    constexpr int kBuf = ((MT + 1) / 2) * 16 * kRowsChunk<MT>;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nl = lane & 15, q = lane >> 4;
@@ -1172,10 +1184,7 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
     const uint16_t *x = dp->x;
     const int rot = (blockIdx.x * 5) % KS;
 
-    // staging role: token row (t/32 + 8*j), 16-byte chunk t%32
-    const int srow = threadIdx.x >> 5, schunk = threadIdx.x & 31;
-    char *xdst = xtile + srow * 528 + schunk * 16;
-    const char *xop = xtile + nl * 528 + q * 16;
+    const char *xop = xtile + nl * kRowsChunk<MT> + q * 16;
 
     floatx4 yacc[RTW][MT];
 #pragma unroll
@@ -1184,16 +1193,6 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
         for (int mt = 0; mt < MT; ++mt) yacc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     auto step_of = [&](int i) { int ks = i + rot; return ks >= KS ? ks - KS : ks; };
-    auto load_x = [&](uintx4 (&st)[XL], int ks) {
-        int kc = ks * kStepK + schunk * 8;
-        kc = kc < K ? kc : kc - 128;                 // padded half record: its trits are zero
-#pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            int m = srow + 8 * j;
-            m = m < M ? m : M - 1;
-            st[j] = load_global<uintx4>(x + static_cast<size_t>(m) * K + kc);
-        }
-    };
     auto load_rec = [&](StepRegs (&r)[RTW], int ks) {
 #pragma unroll
         for (int t = 0; t < RTW; ++t) {
@@ -1210,7 +1209,7 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
             half8 a[2][MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                a[0][mt] = __builtin_bit_cast(half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * 528));
+                a[0][mt] = __builtin_bit_cast(half8, *reinterpret_cast<const uintx4 *>(xb + rows_operand_offset<MT>(mt, 0)));
 #pragma unroll
             for (int f = 0; f < 8; ++f) {
                 const int g2 = f >> 2, fm = f & 3;
@@ -1219,7 +1218,7 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
                         a[(f + 1) & 1][mt] = __builtin_bit_cast(
-                            half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * 528 + (f + 1) * 64));
+                            half8, *reinterpret_cast<const uintx4 *>(xb + rows_operand_offset<MT>(mt, f + 1)));
                 }
                 half8 b[2][RTW];
 #pragma unroll
@@ -1257,7 +1256,7 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const half8 a = __builtin_bit_cast(
-                        half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * 528 + g2 * 256 + fm * 64));
+                        half8, *reinterpret_cast<const uintx4 *>(xb + rows_operand_offset<MT>(mt, g2 * 4 + fm)));
 #pragma unroll
                     for (int t = 0; t < RTW; ++t) {
                         acc1[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b1[t], acc1[t][mt], 0, 0, 0);
@@ -1280,32 +1279,43 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
             }
         }
     };
-    auto publish = [&](const uintx4 (&st)[XL], int buf) {
-        char *d = xdst + buf * kBuf;
+    // staging role: wave w brings in chunks w, w+4, ... of the step; lane t*32+p: piece p of token c + 16*t
+    auto stage_direct = [&](int ks, int buf) {
+        constexpr int NCH = 16 * ((MT + 1) / 2);
+        int kc = ks * kStepK + (lane & 31) * 8;
+        kc = kc < K ? kc : kc - 128;                 // padded half record: its trits are zero
+        if (MT > 1 || lane < 32) {                   // 16 tokens or fewer: the second token of a chunk does not exist
 #pragma unroll
-        for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(d + j * 8 * 528) = st[j];
+            for (int j = 0; j < NCH / 4; ++j) {
+                const int c = w + 4 * j;             // chunk of the step
+                int m = (c >> 4) * 32 + (c & 15) + (lane >> 5) * 16;
+                m = m < M ? m : M - 1;               // rows past M: duplicates, never stored
+                asm volatile("" : "+v"(m));          // keep the row address out of loop-invariant registers
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(x + static_cast<size_t>(m) * K + kc),
+                    (__attribute__((address_space(3))) void *)(xtile + buf * kBuf + c * kRowsChunk<MT>), 16, 0, 0);
+            }
+        }
     };
 
-    uintx4 stage[XL];
     StepRegs ra[RTW], rb[RTW];
-    load_x(stage, step_of(0));
+    stage_direct(step_of(0), 0);
     load_rec(ra, step_of(0));
 #pragma unroll
     for (int t = 0; t < RTW; ++t) rb[t] = ra[t];
-    publish(stage, 0);
+    __builtin_amdgcn_s_waitcnt(0);               // this wave's chunks have landed in LDS
     __syncthreads();
-    // two steps per trip so that the record registers ping-pong without copies
     for (int i = 0; i < KS; i += 2) {
         const bool m1 = i + 1 < KS, m2 = i + 2 < KS;
-        if (m1) { load_x(stage, step_of(i + 1)); load_rec(rb, step_of(i + 1)); }
+        if (m1) { stage_direct(step_of(i + 1), 1); load_rec(rb, step_of(i + 1)); }
         compute(ra, 0);
-        if (m1) publish(stage, 1);
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (m1) {
-                if (m2) { load_x(stage, step_of(i + 2)); load_rec(ra, step_of(i + 2)); }
-                compute(rb, 1);
-                if (m2) publish(stage, 0);
-                __syncthreads();
+            if (m2) { stage_direct(step_of(i + 2), 0); load_rec(ra, step_of(i + 2)); }
+            compute(rb, 1);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
         }
     }
 
@@ -1332,7 +1342,7 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
 template <int MT, int RTW, bool FOLD>
 hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStream_t stream)
 {
-    const size_t lds = 2 * static_cast<size_t>(MT) * 16 * 528;
+    const size_t lds = 2 * static_cast<size_t>((MT + 1) / 2) * 16 * kRowsChunk<MT>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW, FOLD>),
