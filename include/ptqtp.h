@@ -271,8 +271,8 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
  * "small_fold" (ptqtp_gemm_batch with two row tiles per wave: 1 = multiply the group scales into the
  * expanded trits before the matrix pipe, 0 = rescale the per-group sums after it, -1 = default: before for
  * more than 16 tokens), "tile" (1 = use an MFMA tile for every batch > 1, -1 = default), "tile_variant"
- * (1 = always the 256 x 128 tile, 2 = always the 128 x 128 two-waves-per-SIMD tile, 3 = always the
- * 256 x 256 tile with direct-to-LDS activation loads, 0 = default: by problem size);
+ * (workgroup tile, rows x tokens: 1 = 256 x 128, 2 = 128 x 128, 3 = 256 x 256, 4 = 128 x 64, 5 = 64 x 64,
+ * 0 = default: the cheapest by a cost model of the problem size);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
  * unknown key or out-of-range value.  Not thread-safe.
  */

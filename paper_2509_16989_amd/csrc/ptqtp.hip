@@ -518,7 +518,7 @@ gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict
 // fp32 accumulator -- then issues 8*MTW MFMAs per 32-column field against MTW LDS operand reads.
 // Workgroups are numbered so that all token blocks of a row block run on the same XCD and
 // share its L2 copy of the packed rows.
-constexpr int kTileXStride = 272;                   // bytes per token row of the LDS x tile (128 fp16 + pad)
+constexpr int kTileChunk = 1040;                    // 1 KiB chunk of four tokens + 16-byte skew (tiles with direct-to-LDS loads)
 
 __device__ __forceinline__ half8 decode8(uint32_t word, int parity) {
     const uint32_t fp4 = (parity ? (word << 1) : word) & 0xAAAAAAAAu;
@@ -529,25 +529,27 @@ __device__ __forceinline__ half8 decode8(uint32_t word, int parity) {
     return half8{h0.x, h0.y, h1.x, h1.y, h2.x, h2.y, h3.x, h3.y};
 }
 
-struct TileRecs {               // the records of a wave's four row tiles for one 256-column step
-    uintx4 p1[4], p2[4];
-    uintx2 sc[4];
+template <int RTW>
+struct TileRecs {               // the records of a wave's RTW row tiles for one 256-column step
+    uintx4 p1[RTW], p2[RTW];
+    uintx2 sc[RTW];
 };
 
-// MTW = token tiles per wave (4 or 8).  The four waves of a workgroup sit along the rows:
-// workgroup tile = 256 rows x 16*MTW tokens.
+// MTW = token tiles per wave (4 or 8), RTW = row tiles per wave (4, 2 or 1).  The four waves of a workgroup sit
+// along the rows: workgroup tile = 64*RTW rows x 16*MTW tokens.  The smaller tiles are for problems that would
+// otherwise leave most CUs without a workgroup (short prompts on 8B-sized layers).
 // FUSE: the two planes are summed before the matrix pipe, w16 = fp16(alpha1*t1 + alpha2*t2): both
 // products are exact in fp16, so this is ONE rounding per weight (the "dequantization" forward of
 // Sec. "Inference Efficiency": the weight is rebuilt, here per 32-column field in registers) and
 // half the MFMAs.
-template <int MTW, bool FUSE>
+template <int MTW, bool FUSE, int RTW>
 __global__ void __launch_bounds__(256)
 gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB, int nb0)
 {
-    extern __shared__ char xt[];                     // [2][TM][kTileXStride]
-    constexpr int TM = 16 * MTW, NRT = 16;           // tokens, row tiles per workgroup
-    constexpr int XL = TM / 16;                      // 16-byte x loads per thread per group
+    extern __shared__ char xt[];                     // [2][TM/4 chunks][kTileChunk]
+    constexpr int TM = 16 * MTW, NRT = 4 * RTW;      // tokens, row tiles per workgroup
+    constexpr int kBuf = (TM / 4) * kTileChunk;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nl = lane & 15, q = lane >> 4;
@@ -555,38 +557,44 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     const int nb = nb0 + (slot / MB) * 8 + xcd, mb = slot % MB;   // this launch covers row blocks nb0 .. NB-1
     if (nb >= NB) return;                            // whole workgroup, before any barrier
     const int m0 = mb * TM;
-    const int rt_base = nb * NRT + w * 4;
+    const int rt_base = nb * NRT + w * RTW;
     const int NG = K / 128;
 
-    // staging role: thread t loads token row (t/16 + 16*j), 16-byte chunk t%16 of the group's 256 bytes
-    const int srow = threadIdx.x >> 4, schunk = threadIdx.x & 15;
-    const uint16_t *xsrc[XL];
+    // staging (global -> LDS directly): wave w brings in chunks w, w+4, ... of the group; a chunk is the 256-byte group
+    // slice of four tokens, lane t*16+p bringing 16-byte piece p of token c%16 + 16*t of 64-token block c/16
+    const uint16_t *xcol = x + (lane & 15) * 8;
+    auto stage = [&](int g, int buf) {
 #pragma unroll
-    for (int j = 0; j < XL; ++j) {
-        int m = m0 + srow + 16 * j;
-        m = m < M ? m : M - 1;                       // rows past M: duplicates, never stored
-        xsrc[j] = x + static_cast<size_t>(m) * K + schunk * 8;
-    }
-    char *xdst = xt + srow * kTileXStride + schunk * 16;
-    const char *xop = xt + nl * kTileXStride + q * 16;
+        for (int j = 0; j < TM / 16; ++j) {
+            const int c = w + 4 * j;
+            int m = m0 + (c >> 4) * 64 + (c & 15) + (lane >> 4) * 16;
+            m = m < M ? m : M - 1;                   // rows past M: duplicates, never stored
+            asm volatile("" : "+v"(m));              // recompute the row address here instead of keeping TM/16 of them
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(xcol + static_cast<size_t>(m) * K + g * 128),
+                (__attribute__((address_space(3))) void *)(xt + buf * kBuf + c * kTileChunk), 16, 0, 0);
+        }
+    };
+    // operand of token tile mt: tokens (mt%4)*16 + nl of block mt/4 -> chunk nl, run mt%4
+    const char *xop = xt + nl * kTileChunk + q * 16;
 
-    const uint8_t *rec[4];
+    const uint8_t *rec[RTW];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < RTW; ++r) {
         int rt = rt_base + r;
         rt = rt < RT ? rt : RT - 1;
         rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes;
     }
 
-    floatx4 acc[4][MTW];
+    floatx4 acc[RTW][MTW];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < RTW; ++r)
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    auto load_recs = [&](TileRecs &t, int ks) {
+    auto load_recs = [&](TileRecs<RTW> &t, int ks) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < RTW; ++r) {
             const uint8_t *p = rec[r] + static_cast<size_t>(ks) * kRecordBytes;
             t.p1[r] = load_global<uintx4>(p + lane * 16);
             t.p2[r] = load_global<uintx4>(p + kPlaneBytes + lane * 16);
@@ -594,32 +602,26 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
         }
     };
 
-    uintx4 stage[XL];
-    TileRecs ra, rb;
-#pragma unroll
-    for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j]);
+    TileRecs<RTW> ra, rb;
+    stage(0, 0);
     load_recs(ra, 0);
     rb = ra;
-#pragma unroll
-    for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(xdst + j * 16 * kTileXStride) = stage[j];
+    __builtin_amdgcn_s_waitcnt(0);                   // this wave's chunks have landed in LDS
     __syncthreads();
 
     // one 256-column step: two scale groups from `cur`, while `nxt` is filled for step ks+1
-    auto step = [&](const TileRecs &cur, TileRecs &nxt, int ks) {
+    auto step = [&](const TileRecs<RTW> &cur, TileRecs<RTW> &nxt, int ks) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int g = ks * 2 + h;
             if (g < NG) {
                 const bool more = g + 1 < NG;
-                if (more) {
-#pragma unroll
-                    for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j] + (g + 1) * 128);
-                }
+                if (more) stage(g + 1, (g + 1) & 1);
                 if (h == 0 && ks + 1 < KS) load_recs(nxt, ks + 1);
-                const char *xb = xop + (g & 1) * (TM * kTileXStride);
-                half8 al1[4], al2[4];
+                const char *xb = xop + (g & 1) * kBuf;
+                half8 al1[RTW], al2[RTW];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
+                for (int r = 0; r < RTW; ++r) {
                     const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (cur.sc[r].x >> 16) : (cur.sc[r].x & 0xffffu)));
                     const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (cur.sc[r].y >> 16) : (cur.sc[r].y & 0xffffu)));
                     al1[r] = half8{a1, a1, a1, a1, a1, a1, a1, a1};
@@ -628,11 +630,11 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
                 // software pipeline over the four 32-column fields of the group: while the MFMAs of
                 // field fm run, the operands of field fm+1 are read from LDS and its trits expanded
                 constexpr int NPL = FUSE ? 1 : 2;
-                half8 bq[2][NPL][4], aq[2][MTW];
-                auto expand = [&](half8 (&b)[NPL][4], int fm) {
+                half8 bq[2][NPL][RTW], aq[2][MTW];
+                auto expand = [&](half8 (&b)[NPL][RTW], int fm) {
                     const int wi = 2 * h + (fm >> 1), par = fm & 1;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
+                    for (int r = 0; r < RTW; ++r) {
                         if constexpr (FUSE) {
                             b[0][r] = decode8(cur.p1[r][wi], par) * al1[r] + decode8(cur.p2[r][wi], par) * al2[r];
                         } else {
@@ -645,7 +647,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
 #pragma unroll
                     for (int mt = 0; mt < MTW; ++mt)
                         a[mt] = __builtin_bit_cast(
-                            half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * kTileXStride + fm * 64));
+                            half8, *reinterpret_cast<const uintx4 *>(xb + (mt >> 2) * (16 * kTileChunk) + (mt & 3) * 256 + fm * 64));
                 };
                 // (measured: pays with one MFMA set per field; with two the plain order is as fast)
                 constexpr bool AHEAD = FUSE;
@@ -663,14 +665,10 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
 #pragma unroll
                         for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
-                            for (int r = 0; r < 4; ++r)
+                            for (int r = 0; r < RTW; ++r)
                                 acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq[fm & 1][mt], bq[fm & 1][pl][r], acc[r][mt], 0, 0, 0);
                 }
-                if (more) {
-                    char *d = xdst + ((g + 1) & 1) * (TM * kTileXStride);
-#pragma unroll
-                    for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(d + j * 16 * kTileXStride) = stage[j];
-                }
+                __builtin_amdgcn_s_waitcnt(0);       // the next group's chunks (and records) have landed
                 __syncthreads();
             }
         }
@@ -682,7 +680,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     }
 
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < RTW; ++r) {
         const int rt = rt_base + r;
         const int n = rt * kTileRows + nl;
         if (rt < RT && n < N) {
@@ -691,154 +689,6 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int m = m0 + mt * 16 + 4 * q + j;
-                    if (m < M) {
-                        const size_t off = static_cast<size_t>(m) * N + n;
-                        if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(acc[r][mt][j]);
-                        else reinterpret_cast<float *>(y)[off] = acc[r][mt][j];
-                    }
-                }
-        }
-    }
-}
-
-// Variant with two waves per SIMD: workgroup = 2 x 2 waves, each 4 row tiles x 4 token tiles
-// (128 rows x 128 tokens per workgroup), the record words of a scale group fetched just in time
-// (8 bytes per lane, plane and row tile) so that a wave fits in 256 registers and two workgroups
-// share a CU: while one waits at its barrier the other keeps the matrix pipe busy.
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-gemm_tile2_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
-                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB)
-{
-    extern __shared__ char xt[];                     // [2][128][kTileXStride]
-    constexpr int TM = 128, NRT = 8, XL = 8;
-    const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nl = lane & 15, q = lane >> 4;
-    const int wm = w & 1, wn = w >> 1;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int nb = (slot / MB) * 8 + xcd, mb = slot % MB;
-    if (nb >= NB) return;                            // whole workgroup, before any barrier
-    const int m0 = mb * TM;
-    const int rt_base = nb * NRT + wn * 4;
-    const int NG = K / 128;
-
-    const int srow = threadIdx.x >> 4, schunk = threadIdx.x & 15;
-    const uint16_t *xsrc[XL];
-#pragma unroll
-    for (int j = 0; j < XL; ++j) {
-        int m = m0 + srow + 16 * j;
-        m = m < M ? m : M - 1;
-        xsrc[j] = x + static_cast<size_t>(m) * K + schunk * 8;
-    }
-    char *xdst = xt + srow * kTileXStride + schunk * 16;
-    const char *xop = xt + (wm * 64 + nl) * kTileXStride + q * 16;
-
-    const uint8_t *rec[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        int rt = rt_base + r;
-        rt = rt < RT ? rt : RT - 1;
-        rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes + lane * 16;
-    }
-
-    floatx4 acc[4][4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    // words of group g: record g/2, half g%2 -> 8 bytes per lane, plane and row tile; scales: 4 fp16 per row
-    auto load_group = [&](uintx2 (&pw)[4][2], uintx2 (&sc)[4], int g) {
-        const size_t off = static_cast<size_t>(g >> 1) * kRecordBytes + (g & 1) * 8;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            pw[r][0] = load_global<uintx2>(rec[r] + off);
-            pw[r][1] = load_global<uintx2>(rec[r] + off + kPlaneBytes);
-            sc[r] = load_global<uintx2>(rec[r] - lane * 16 + static_cast<size_t>(g >> 1) * kRecordBytes + 2 * kPlaneBytes + nl * 8);
-        }
-    };
-    auto compute = [&](const uintx2 (&pw)[4][2], const uintx2 (&sc)[4], int g) {
-        const char *xb = xop + (g & 1) * (TM * kTileXStride);
-        const int h = g & 1;
-        half8 al[4][2];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].x >> 16) : (sc[r].x & 0xffffu)));
-            const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].y >> 16) : (sc[r].y & 0xffffu)));
-            al[r][0] = half8{a1, a1, a1, a1, a1, a1, a1, a1};
-            al[r][1] = half8{a2, a2, a2, a2, a2, a2, a2, a2};
-        }
-#pragma unroll
-        for (int fm = 0; fm < 4; ++fm) {
-            half8 b[2][4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl)
-                    b[pl][r] = decode8((fm >> 1) ? pw[r][pl].y : pw[r][pl].x, fm & 1) * al[r][pl];
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                const half8 a = __builtin_bit_cast(
-                    half8, *reinterpret_cast<const uintx4 *>(xb + mt * 16 * kTileXStride + fm * 64));
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[pl][r], acc[r][mt], 0, 0, 0);
-            }
-        }
-    };
-
-    uintx4 stage[XL];
-    uintx2 pa[4][2], pb[4][2], sa[4], sb[4];
-#pragma unroll
-    for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j]);
-    load_group(pa, sa, 0);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) { pb[r][0] = pa[r][0]; pb[r][1] = pa[r][1]; sb[r] = sa[r]; }
-#pragma unroll
-    for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(xdst + j * 16 * kTileXStride) = stage[j];
-    __syncthreads();
-
-    for (int g = 0; g < NG; g += 2) {
-        const bool m1 = g + 1 < NG, m2 = g + 2 < NG;
-        if (m1) {
-#pragma unroll
-            for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j] + (g + 1) * 128);
-            load_group(pb, sb, g + 1);
-        }
-        compute(pa, sa, g);
-        if (m1) {
-            char *d = xdst + TM * kTileXStride;
-#pragma unroll
-            for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(d + j * 16 * kTileXStride) = stage[j];
-        }
-        __syncthreads();
-        if (m1) {
-            if (m2) {
-#pragma unroll
-                for (int j = 0; j < XL; ++j) stage[j] = load_global<uintx4>(xsrc[j] + (g + 2) * 128);
-                load_group(pa, sa, g + 2);
-            }
-            compute(pb, sb, g + 1);
-            if (m2) {
-#pragma unroll
-                for (int j = 0; j < XL; ++j) *reinterpret_cast<uintx4 *>(xdst + j * 16 * kTileXStride) = stage[j];
-            }
-            __syncthreads();
-        }
-    }
-
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int rt = rt_base + r;
-        const int n = rt * kTileRows + nl;
-        if (rt < RT && n < N) {
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int m = m0 + wm * 64 + mt * 16 + 4 * q + j;
                     if (m < M) {
                         const size_t off = static_cast<size_t>(m) * N + n;
                         if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(acc[r][mt][j]);
@@ -1023,48 +873,75 @@ hipError_t launch_gemm_tile3(const uint8_t *records, const uint16_t *x, void *y,
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_tile2(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
-                             hipStream_t stream)
-{
-    constexpr int TM = 128, NRT = 8;
-    const int MB = (M + TM - 1) / TM;
-    const int NB = static_cast<int>((s.RT + NRT - 1) / NRT);
-    const int64_t grid = static_cast<int64_t>((NB + 7) / 8) * 8 * MB;
-    const size_t lds = 2 * static_cast<size_t>(TM) * kTileXStride;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile2_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
-    hipLaunchKernelGGL(gemm_tile2_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x, y, M,
-                       static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT), static_cast<int>(s.KS),
-                       y_f16, MB, NB);
-    return hipGetLastError();
-}
-
-// row blocks (of 256 rows) nb0 .. nb1-1; nb1 < 0: to the end
-template <int MTW, bool FUSE>
+// row blocks (of 64*RTW rows) nb0 .. nb1-1; nb1 < 0: to the end
+template <int MTW, bool FUSE, int RTW = 4>
 hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
                             hipStream_t stream, int nb0 = 0, int nb1 = -1)
 {
-    constexpr int TM = 16 * MTW, NRT = 16;
+    constexpr int TM = 16 * MTW, NRT = 4 * RTW;
     const int MB = (M + TM - 1) / TM;
     const int NB = nb1 >= 0 ? nb1 : static_cast<int>((s.RT + NRT - 1) / NRT);
     const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
-    const size_t lds = 2 * static_cast<size_t>(TM) * kTileXStride;
+    const size_t lds = 2 * static_cast<size_t>(TM / 4) * kTileChunk;
     static bool configured = false;                  // raise the dynamic LDS limit once per process
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<MTW, FUSE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<MTW, FUSE, RTW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((gemm_tile_kernel<MTW, FUSE>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
+    hipLaunchKernelGGL((gemm_tile_kernel<MTW, FUSE, RTW>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
                        static_cast<int>(s.KS), y_f16, MB, NB, nb0);
     return hipGetLastError();
+}
+
+// The prefill tiles, largest first.  `units` = 16 x 16 output tiles per workgroup / 2 (one unit = the MFMA work of
+// two row tiles x one token tile per field).  Times in microseconds per 32 scale groups, measured on 8B and 70B
+// layer shapes: `lone` = a workgroup alone on its CU (the latency floor of the K loop), `rate` = per unit when the
+// CU's matrix pipes are the limit; index 0 = both planes through the matrix pipe, 1 = planes summed first.
+struct TileKind {
+    int row_tiles, tokens, units;
+    float lone[2], rate[2];
+};
+constexpr int kTileKindCount = 5;
+constexpr TileKind kTileKinds[kTileKindCount] = {
+    {16, 256, 256, {167.f, 121.f}, {0.73f, 0.50f}},   // gemm_tile3_kernel
+    {16, 128, 128, {97.f, 66.f}, {0.77f, 0.53f}},     // gemm_tile_kernel<8, ., 4>
+    {8, 128, 64, {55.f, 44.f}, {0.75f, 0.54f}},       // gemm_tile_kernel<8, ., 2>
+    {8, 64, 32, {32.f, 28.f}, {0.83f, 0.65f}},        // gemm_tile_kernel<4, ., 2>
+    {4, 64, 16, {24.f, 22.f}, {1.13f, 0.90f}},        // gemm_tile_kernel<4, ., 1>
+};
+constexpr double kTileLaunchCost = 3.0;               // a second launch, same scale
+
+// Estimated time of one launch of tile kind k over `row_tiles` row tiles and M tokens: the busiest CU holds
+// ceil(workgroups / 256) of them, and never finishes before one workgroup's K loop has run.
+double tile_cost(int k, int fused, int row_tiles, int M)
+{
+    const TileKind &t = kTileKinds[k];
+    const int64_t wgs = static_cast<int64_t>((row_tiles + t.row_tiles - 1) / t.row_tiles) * ((M + t.tokens - 1) / t.tokens);
+    const double busy = static_cast<double>((wgs + 255) / 256) * t.units * t.rate[fused];
+    return busy > t.lone[fused] ? busy : t.lone[fused];
+}
+
+// Launch tile kind k over row tiles rt0 .. rt1-1 (rt0 a multiple of 16; rt1 < 0: to the end, else a multiple of 16).
+hipError_t launch_tile_kind(int k, bool fuse, const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s,
+                            int y_f16, hipStream_t stream, int rt0, int rt1)
+{
+    const int per = kTileKinds[k].row_tiles;
+    const int nb0 = rt0 / per, nb1 = rt1 < 0 ? -1 : rt1 / per;
+#define PTQTP_TILE(MTW_, RTW_)                                                                         \
+    (fuse ? launch_gemm_tile<MTW_, true, RTW_>(records, x, y, M, s, y_f16, stream, nb0, nb1)           \
+          : launch_gemm_tile<MTW_, false, RTW_>(records, x, y, M, s, y_f16, stream, nb0, nb1))
+    switch (k) {
+        case 0: return fuse ? launch_gemm_tile3<true>(records, x, y, M, s, y_f16, stream, nb0, nb1)
+                            : launch_gemm_tile3<false>(records, x, y, M, s, y_f16, stream, nb0, nb1);
+        case 1: return PTQTP_TILE(8, 4);
+        case 2: return PTQTP_TILE(8, 2);
+        case 3: return PTQTP_TILE(4, 2);
+        default: return PTQTP_TILE(4, 1);
+    }
+#undef PTQTP_TILE
 }
 
 int g_tune_small_waves = 0, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0, g_tune_small_fold = -1;
@@ -1414,33 +1291,39 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
         d.first_item = 0; d.pad = 0;
         e = launch_items<false>(nullptr, d, f16, s.RT, s.KS, stream);
     } else if (M >= 256 || g_tune_tile == 1) {
-        // 256-row x 128-token tiles leave CUs idle on small problems: use the 128 x 128 variant then
-        const int64_t big_tiles = ((s.RT + 15) / 16) * ((M + 127) / 128);
-        // 256 x 256 tiles do ~15 % more work per second than 256 x 128 ones but need enough of them to fill the
-        // 256 CUs in whole rounds: compare the two by (speed x fraction of the last round's CUs that are busy)
-        const int64_t t3 = ((s.RT + 15) / 16) * ((M + 255) / 256);
-        const double eff3 = 1.15 * static_cast<double>(t3) / static_cast<double>((t3 + 255) / 256 * 256);
-        const double eff1 = static_cast<double>(big_tiles) / static_cast<double>((big_tiles + 255) / 256 * 256);
-        // A last round of 256 x 256 tiles that would leave most CUs idle goes to 256 x 128 tiles instead: the first
-        // nb3 row blocks (whole rounds of 256 x 256 tiles) in one launch, the remaining row blocks in a second one
-        const int NB16 = static_cast<int>((s.RT + 15) / 16), MB3 = static_cast<int>((M + 255) / 256);
-        const int64_t whole = t3 / 256 * 256;
-        const int nb3 = static_cast<int>(whole / MB3);
-        if (g_tune_tile_variant == 0 && g_tune_tile != 1 && M >= 256 && whole > 0 && t3 - whole > 0 &&
-            t3 - whole <= 160 && nb3 > 0 && nb3 < NB16) {
-            e = fuse_planes ? launch_gemm_tile3<true>(records, x, y, Mi, s, f16, stream, 0, nb3)
-                            : launch_gemm_tile3<false>(records, x, y, Mi, s, f16, stream, 0, nb3);
-            if (e == hipSuccess)
-                e = fuse_planes ? launch_gemm_tile<8, true>(records, x, y, Mi, s, f16, stream, nb3)
-                                : launch_gemm_tile<8, false>(records, x, y, Mi, s, f16, stream, nb3);
-        } else if (g_tune_tile_variant == 3 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && M >= 256 && eff3 >= eff1))
-            e = fuse_planes ? launch_gemm_tile3<true>(records, x, y, Mi, s, f16, stream)
-                            : launch_gemm_tile3<false>(records, x, y, Mi, s, f16, stream);
-        else if (!fuse_planes && (g_tune_tile_variant == 2 || (g_tune_tile_variant == 0 && g_tune_tile != 1 && big_tiles < 256)))
-            e = launch_gemm_tile2(records, x, y, Mi, s, f16, stream);
-        else if (M <= 64) e = launch_gemm_tile<4, false>(records, x, y, Mi, s, f16, stream);
-        else if (fuse_planes) e = launch_gemm_tile<8, true>(records, x, y, Mi, s, f16, stream);
-        else e = launch_gemm_tile<8, false>(records, x, y, Mi, s, f16, stream);
+        const int fz = fuse_planes ? 1 : 0;
+        const int RTi = static_cast<int>(s.RT);
+        if (g_tune_tile_variant != 0) {
+            static const int kind_of_variant[6] = {0, 1, 2, 0, 3, 4};
+            e = launch_tile_kind(kind_of_variant[g_tune_tile_variant], fuse_planes, records, x, y, Mi, s, f16, stream, 0, -1);
+        } else {
+            // one launch of the cheapest tile ...
+            int best = 1, best_rest = -1, split_rt = 0;
+            double cost = 1e30;
+            for (int k = 0; k < kTileKindCount; ++k) {
+                const double c = tile_cost(k, fz, RTi, Mi);
+                if (c < cost) { cost = c; best = k; }
+            }
+            // ... or whole rounds of 256 x 256 tiles for the first row blocks, then the cheapest smaller tile for the
+            // rest, when the last round of big tiles would leave most CUs idle
+            const int MB3 = (Mi + 255) / 256, NB16 = (RTi + 15) / 16;
+            const int64_t t3 = static_cast<int64_t>(NB16) * MB3;
+            const int nb3 = static_cast<int>(t3 / 256 * 256 / MB3);
+            if (nb3 > 0 && nb3 < NB16) {
+                const double head = tile_cost(0, fz, nb3 * 16, Mi);
+                for (int k = 1; k < kTileKindCount; ++k) {
+                    const double c = head + tile_cost(k, fz, RTi - nb3 * 16, Mi) + kTileLaunchCost;
+                    if (c < cost) { cost = c; best = 0; best_rest = k; split_rt = nb3 * 16; }
+                }
+            }
+            if (best_rest < 0) {
+                e = launch_tile_kind(best, fuse_planes, records, x, y, Mi, s, f16, stream, 0, -1);
+            } else {
+                e = launch_tile_kind(0, fuse_planes, records, x, y, Mi, s, f16, stream, 0, split_rt);
+                if (e == hipSuccess)
+                    e = launch_tile_kind(best_rest, fuse_planes, records, x, y, Mi, s, f16, stream, split_rt, -1);
+            }
+        }
     } else if (M > PTQTP_GEMM_SMALL_MAX_M) {
         // 65..255 tokens: too few token blocks to fill the chip with 256-row tiles; run the
         // small-batch kernel on chunks of 64 tokens instead
@@ -1672,7 +1555,7 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
         return PTQTP_OK;
     }
     if (!strcmp(key, "tile_variant")) {
-        if (value < 0 || value > 3) return PTQTP_ERR_SHAPE;
+        if (value < 0 || value > 5) return PTQTP_ERR_SHAPE;
         g_tune_tile_variant = value;
         return PTQTP_OK;
     }

@@ -376,7 +376,7 @@ def test_gemm_tile_variants(ptq, N, K, M):
     x = workloads.make_x(M, K, 73, N, M)
     packed = pack(ptq, lin)
     ys = []
-    for variant in (1, 2, 3):                      # 256 x 128 tile, 128 x 128 tile, 256 x 256 tile
+    for variant in (1, 2, 3, 4, 5, 0):             # 256x128, 128x128, 256x256, 128x64, 64x64 tiles, default choice
         try:
             ptq.ptqtp_tune("tile_variant", variant)
             y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
@@ -386,7 +386,7 @@ def test_gemm_tile_variants(ptq, N, K, M):
         check(y, lin, x, tight=3e-5)
         ys.append(y)
     # every tile feeds each accumulator the same MFMA sequence: identical bits
-    assert torch.equal(ys[0], ys[1]) and torch.equal(ys[0], ys[2])
+    assert all(torch.equal(ys[0], y) for y in ys[1:])
 
 
 @pytest.mark.parametrize("M", [2, 16, 33, 64])
@@ -411,7 +411,7 @@ def test_gemm_fused_planes_matches_rounded_weight_oracle(ptq, N, K, M):
     x = workloads.make_x(M, K, 73, N, M)
     ref_f, B_f = oracle.forward_fused(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
     ref, B = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
-    for variant in (0, 1, 3):                      # default choice, 256 x 128 tile, 256 x 256 tile
+    for variant in (0, 1, 2, 3, 4, 5):             # default choice, then every tile
         try:
             ptq.ptqtp_tune("tile_variant", variant)
             y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
@@ -486,7 +486,7 @@ def test_gemm_tile_prefill_70b_sampled(ptq, name, flag):
 @pytest.mark.parametrize("flag", [0, 16])
 def test_gemm_prefill_split_between_tile_sizes(ptq, flag):
     # 36 row blocks x 8 token blocks = 288 tiles of 256 x 256: the first 256 go to that tile, the last four row blocks
-    # (rows 8192..9215) to 256 x 128 tiles in a second launch; rows on both sides of the seam are checked
+    # (rows 8192..9215) to smaller tiles in a second launch; rows on both sides of the seam are checked
     N, K, M = 9216, 256, 2048
     lin = workloads.make_linear(N, K, 77, 1)
     x = workloads.make_x(M, K, 77, 2)
@@ -502,6 +502,28 @@ def test_gemm_prefill_split_between_tile_sizes(ptq, flag):
     else:
         ref, B = oracle.forward(*sub, x[toks], threads=8)
     assert np.all(np.abs(got - ref) <= TIGHT * B), f"{(np.abs(got - ref) / B).max():.3e}"
+
+
+@pytest.mark.parametrize("name,M,flag", [("q", 256, 0), ("q", 512, 0), ("k", 256, 0), ("k", 1024, 16), ("down", 256, 0),
+                                         ("down", 512, 16), ("gate", 256, 0)])
+def test_gemm_short_prompt_8b_sampled(ptq, name, M, flag):
+    # short prompts on 8B-shaped projections: too few 256-row tiles to fill the chip, so the default choice is one of
+    # the smaller tiles; sampled rows and tokens against the oracle
+    lin = workloads.linear_8b(name)
+    N, K = lin["N"], lin["K"]
+    x = workloads.x_for(name, M, K, config=1)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=flag, out=y)
+    assert bool(torch.isfinite(y).all())
+    rows = np.unique(np.concatenate([[0, 63, 64, 127, 128, N - 1], np.random.default_rng(14).integers(0, N, 48)]))
+    toks = np.unique(np.concatenate([[0, 63, 64, 127, 128, M - 1], np.random.default_rng(15).integers(0, M, 24)]))
+    sub = (lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows])
+    got = y.cpu().numpy().astype(np.float64)[np.ix_(toks, rows)]
+    ref, B = oracle.forward(*sub, x[toks], threads=8)
+    assert np.all(np.abs(got - ref) <= TOL * B)
+    if flag:
+        ref, B = oracle.forward_fused(*sub, x[toks])
+    assert np.all(np.abs(got - ref) <= 3e-5 * B), f"{(np.abs(got - ref) / B).max():.3e}"
 
 
 def test_gemm_small_rows_match_gemv(ptq):
