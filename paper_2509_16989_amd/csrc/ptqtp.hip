@@ -924,6 +924,26 @@ double tile_cost(int k, int fused, int row_tiles, int M)
     return busy > t.lone[fused] ? busy : t.lone[fused];
 }
 
+double best_tile_cost(int row_tiles, int M)
+{
+    double c = 1e30;
+    for (int k = 0; k < kTileKindCount; ++k) {
+        const double ck = tile_cost(k, 0, row_tiles, M);
+        c = ck < c ? ck : c;
+    }
+    return c;
+}
+
+// The small-batch kernel on chunks of 64 tokens, in microseconds: a full chunk streams the packed rows once (0.037 per
+// row tile and 32 groups, at least 11 for the launch and its ramp); a last chunk of up to 16 / 32 tokens uses the narrower kernels.
+double small_cost(int row_tiles, int groups, int M)
+{
+    const double stream = 0.037 * row_tiles * groups / 32.0;
+    const double full = stream > 11.0 ? stream : 11.0;
+    const int rest = M % 64;
+    return (M / 64) * full + (rest == 0 ? 0.0 : rest > 32 ? full : rest > 16 ? 0.6 * full : 0.4 * full);
+}
+
 // Launch tile kind k over row tiles rt0 .. rt1-1 (rt0 a multiple of 16; rt1 < 0: to the end, else a multiple of 16).
 hipError_t launch_tile_kind(int k, bool fuse, const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s,
                             int y_f16, hipStream_t stream, int rt0, int rt1)
@@ -944,7 +964,7 @@ hipError_t launch_tile_kind(int k, bool fuse, const uint8_t *records, const uint
 #undef PTQTP_TILE
 }
 
-int g_tune_small_waves = 0, g_tune_tile = -1, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0, g_tune_small_fold = -1;
+int g_tune_small_waves = 0, g_tune_tile = 0, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0, g_tune_small_fold = -1;
 
 template <int MT, int R, int S, bool PLAN, int ML>
 hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records, const uint16_t *x, void *y, int M,
@@ -1290,7 +1310,10 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
         d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
         d.first_item = 0; d.pad = 0;
         e = launch_items<false>(nullptr, d, f16, s.RT, s.KS, stream);
-    } else if (M >= 256 || g_tune_tile == 1) {
+    } else if (M >= 256 || g_tune_tile == 1 ||
+               (g_tune_tile == 0 && M > 32 &&
+                best_tile_cost(static_cast<int>(s.RT), Mi) * static_cast<double>(s.NG) / 32.0 <
+                    small_cost(static_cast<int>(s.RT), static_cast<int>(s.NG), Mi))) {
         const int fz = fuse_planes ? 1 : 0;
         const int RTi = static_cast<int>(s.RT);
         if (g_tune_tile_variant != 0) {

@@ -399,7 +399,7 @@ def test_gemm_tile_forced_for_small_batches(ptq, M):
         y = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K)
         y16 = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K, y_dtype=ptq.PTQTP_F16)
     finally:
-        ptq.ptqtp_tune("tile", -1)
+        ptq.ptqtp_tune("tile", 0)
     check(y, lin, x, tight=3e-5)
     check(y16, lin, x, tight=TIGHT_F16)
 
@@ -463,7 +463,7 @@ def test_gemm_tile_integer_exact_and_general_scales(ptq):
 
 @pytest.mark.parametrize("name,flag", [("k", 0), ("q", 0), ("q", 16)])
 def test_gemm_tile_prefill_70b_sampled(ptq, name, flag):
-    # prefill M = 2048 on 70B-shaped projections (k: 1024 rows, the 128 x 128 tile; q: 8192 rows, the 256 x 256 tile,
+    # prefill M = 2048 on 70B-shaped projections (k: 1024 rows, a small tile; q: 8192 rows, the 256 x 256 tile,
     # also with fused planes); sampled rows and tokens against the oracle
     lin = workloads.linear_70b(name)
     N, K, M = lin["N"], lin["K"], 2048
