@@ -253,7 +253,8 @@ def _graph_time(torch, stream, run, launches, reps=10):
 
 def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False, quick=False):
     """The workloads beside the headline, one linear per launch:
-    each 8B shape at M = 1, 4, 16, 64, cold (walking the 32 layer copies) -- and M = 1 hot;
+    each 8B shape at M = 1, 4, 16, 64, cold (walking the 32 layer copies) -- and M = 1 hot, and short prompts
+    (M = 128, 512) on the small MFMA tiles;
     70B shapes at M = 1 and 32 (hot: one copy) and prefill M = 2048 on the MFMA tiles;
     the whole stack in one launch at M = 4, 16, 64; the dependent decode chain;
     plus the quantizer (ptqtp_quantize) on two 8B shapes, with the oracle quantizer timed on a 256 x 4096 sample."""
@@ -278,6 +279,12 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
             us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blobs[idxs[0]], x, n, k, out=y) for _ in range(32)], 32, reps=reps)
             note(f"8B {name} done")
             res["8b"][f"{name}_{n}x{k}_M1_hot"] = {"us": round(us, 2), "GBps": round(algorithmic_bytes(n, k, 1) / us / 1e3, 1)}
+            # a short prompt (the paper's prefill length, Sec. "Inference Efficiency"): few tiles, the small MFMA tiles
+            for M in (128, 512):
+                x = torch.randn(M, k, device=dev).half()
+                y = torch.empty(M, n, device=dev)
+                us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blobs[idxs[0]], x, n, k, out=y) for _ in range(8)], 8, reps=reps)
+                res["8b"][f"{name}_{n}x{k}_M{M}_prefill"] = {"us": round(us, 2), "TFLOPs": round(4.0 * M * n * k / us / 1e6, 1)}
         for name in ("q", "k", "gate", "down"):
             lin = workloads.linear_70b(name)
             n, k = lin["N"], lin["K"]
