@@ -262,6 +262,20 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Which kernels ptqtp_gemm would run for a shape (host logic only, no GPU needed; for tests and sweeps).
+ * route[0] = PTQTP_ROUTE_*; for PTQTP_ROUTE_TILE route[1] = workgroup tile of the (first) launch
+ * (0 = 256 rows x 256 tokens, 1 = 256 x 128, 2 = 128 x 128, 3 = 128 x 64, 4 = 64 x 64), route[2] = the
+ * row (a multiple of 256) at which a second launch takes over, divided by 16, or 0, route[3] = that second
+ * launch's tile or -1.  The choice never changes what is computed per accumulator within the tile path
+ * (all tiles add the groups in the same order); it follows ptqtp_tune.  y_dtype as for ptqtp_gemm.
+ */
+#define PTQTP_ROUTE_STREAM 0        /* batch 1: streamed rows */
+#define PTQTP_ROUTE_SMALL 1         /* small-batch kernel, one launch */
+#define PTQTP_ROUTE_SMALL_CHUNKS 2  /* small-batch kernel on chunks of 64 tokens */
+#define PTQTP_ROUTE_TILE 3          /* MFMA tile(s) */
+ptqtp_status ptqtp_gemm_route(int64_t M, int64_t N, int64_t K, int32_t group, int32_t y_dtype, int32_t *route);
+
+/*
  * Tuning hook for benchmarks and sweeps (not needed for correct use): override
  * the launch shape the compute calls pick.  key = "stream_waves" (batch 1: waves per item, 1..16),
  * "stream_depth" (batch 1: records in flight per wave: 1, 2 or 4), "small_waves" (one linear at batch > 1:

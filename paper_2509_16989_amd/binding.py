@@ -80,6 +80,8 @@ def _load():
         lib.ptqtp_quantize.argtypes = [p, i64, i64, i32, i32, ctypes.c_double, p, p, p, p, p, p, sz, p]
         lib.ptqtp_tune.restype = i32
         lib.ptqtp_tune.argtypes = [ctypes.c_char_p, i32]
+        lib.ptqtp_gemm_route.restype = i32
+        lib.ptqtp_gemm_route.argtypes = [i64, i64, i64, i32, i32, p]
         _lib = lib
     return _lib
 
@@ -109,6 +111,19 @@ def ptqtp_tune(key: str, value: int) -> None:
     st = _load().ptqtp_tune(key.encode(), int(value))
     if st:
         raise PtqtpError(st, "ptqtp_tune")
+
+
+PTQTP_ROUTE_STREAM, PTQTP_ROUTE_SMALL, PTQTP_ROUTE_SMALL_CHUNKS, PTQTP_ROUTE_TILE = 0, 1, 2, 3
+TILE_SHAPES = ((256, 256), (256, 128), (128, 128), (128, 64), (64, 64))   # rows x tokens per route tile index
+
+
+def ptqtp_gemm_route(M: int, N: int, K: int, group: int = 128, y_dtype: int = PTQTP_F32):
+    """(path, tile, split_row_tile, second_tile): which kernels ptqtp_gemm would run (host logic, no GPU)."""
+    r = (ctypes.c_int32 * 4)()
+    st = _load().ptqtp_gemm_route(int(M), int(N), int(K), int(group), int(y_dtype), r)
+    if st:
+        raise PtqtpError(st, "ptqtp_gemm_route")
+    return tuple(int(v) for v in r)
 
 
 def _stream() -> int:

@@ -1289,6 +1289,53 @@ hipError_t small_batch_stage(const uint8_t *records, const uint16_t *x, void *y,
 namespace {
 
 
+// Which kernels a forward of M > 1 tokens runs (host logic only; ptqtp_gemm_route reports it).
+struct Route {
+    int path;                   // PTQTP_ROUTE_*
+    int kind;                   // tile kind of the (first) launch, index into kTileKinds
+    int split_row_tile;         // two launches: the first covers row tiles below this multiple of 16
+    int second_kind;            // tile kind of the second launch, or -1
+};
+
+Route choose_route(const Shape &s, int M, bool fuse_planes)
+{
+    Route r = {PTQTP_ROUTE_SMALL, -1, 0, -1};
+    const int RT = static_cast<int>(s.RT), NG = static_cast<int>(s.NG);
+    const bool tile = M >= 256 || g_tune_tile == 1 ||
+                      (g_tune_tile == 0 && M > 32 && best_tile_cost(RT, M) * NG / 32.0 < small_cost(RT, NG, M));
+    if (!tile) {
+        // 65..255 tokens without a tile: chunks of 64 tokens
+        r.path = M > PTQTP_GEMM_SMALL_MAX_M ? PTQTP_ROUTE_SMALL_CHUNKS : PTQTP_ROUTE_SMALL;
+        return r;
+    }
+    r.path = PTQTP_ROUTE_TILE;
+    if (g_tune_tile_variant != 0) {
+        static const int kind_of_variant[6] = {0, 1, 2, 0, 3, 4};
+        r.kind = kind_of_variant[g_tune_tile_variant];
+        return r;
+    }
+    const int fz = fuse_planes ? 1 : 0;
+    // one launch of the cheapest tile ...
+    double cost = 1e30;
+    for (int k = 0; k < kTileKindCount; ++k) {
+        const double c = tile_cost(k, fz, RT, M);
+        if (c < cost) { cost = c; r.kind = k; }
+    }
+    // ... or whole rounds of 256 x 256 tiles for the first row blocks, then the cheapest smaller tile for the rest,
+    // when the last round of big tiles would leave most CUs idle
+    const int MB3 = (M + 255) / 256, NB16 = (RT + 15) / 16;
+    const int64_t t3 = static_cast<int64_t>(NB16) * MB3;
+    const int nb3 = static_cast<int>(t3 / 256 * 256 / MB3);
+    if (nb3 > 0 && nb3 < NB16) {
+        const double head = tile_cost(0, fz, nb3 * 16, M);
+        for (int k = 1; k < kTileKindCount; ++k) {
+            const double c = head + tile_cost(k, fz, RT - nb3 * 16, M) + kTileLaunchCost;
+            if (c < cost) { cost = c; r.kind = 0; r.second_kind = k; r.split_row_tile = nb3 * 16; }
+        }
+    }
+    return r;
+}
+
 ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t y_dtype, int64_t M,
                          int64_t N, int64_t K, int32_t group, void *stream_, int64_t max_m, bool fuse_planes = false)
 {
@@ -1310,56 +1357,28 @@ ptqtp_status run_forward(const void *packed, const uint16_t *x, void *y, int32_t
         d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
         d.first_item = 0; d.pad = 0;
         e = launch_items<false>(nullptr, d, f16, s.RT, s.KS, stream);
-    } else if (M >= 256 || g_tune_tile == 1 ||
-               (g_tune_tile == 0 && M > 32 &&
-                best_tile_cost(static_cast<int>(s.RT), Mi) * static_cast<double>(s.NG) / 32.0 <
-                    small_cost(static_cast<int>(s.RT), static_cast<int>(s.NG), Mi))) {
-        const int fz = fuse_planes ? 1 : 0;
-        const int RTi = static_cast<int>(s.RT);
-        if (g_tune_tile_variant != 0) {
-            static const int kind_of_variant[6] = {0, 1, 2, 0, 3, 4};
-            e = launch_tile_kind(kind_of_variant[g_tune_tile_variant], fuse_planes, records, x, y, Mi, s, f16, stream, 0, -1);
-        } else {
-            // one launch of the cheapest tile ...
-            int best = 1, best_rest = -1, split_rt = 0;
-            double cost = 1e30;
-            for (int k = 0; k < kTileKindCount; ++k) {
-                const double c = tile_cost(k, fz, RTi, Mi);
-                if (c < cost) { cost = c; best = k; }
-            }
-            // ... or whole rounds of 256 x 256 tiles for the first row blocks, then the cheapest smaller tile for the
-            // rest, when the last round of big tiles would leave most CUs idle
-            const int MB3 = (Mi + 255) / 256, NB16 = (RTi + 15) / 16;
-            const int64_t t3 = static_cast<int64_t>(NB16) * MB3;
-            const int nb3 = static_cast<int>(t3 / 256 * 256 / MB3);
-            if (nb3 > 0 && nb3 < NB16) {
-                const double head = tile_cost(0, fz, nb3 * 16, Mi);
-                for (int k = 1; k < kTileKindCount; ++k) {
-                    const double c = head + tile_cost(k, fz, RTi - nb3 * 16, Mi) + kTileLaunchCost;
-                    if (c < cost) { cost = c; best = 0; best_rest = k; split_rt = nb3 * 16; }
-                }
-            }
-            if (best_rest < 0) {
-                e = launch_tile_kind(best, fuse_planes, records, x, y, Mi, s, f16, stream, 0, -1);
-            } else {
-                e = launch_tile_kind(0, fuse_planes, records, x, y, Mi, s, f16, stream, 0, split_rt);
-                if (e == hipSuccess)
-                    e = launch_tile_kind(best_rest, fuse_planes, records, x, y, Mi, s, f16, stream, split_rt, -1);
-            }
-        }
-    } else if (M > PTQTP_GEMM_SMALL_MAX_M) {
-        // 65..255 tokens: too few token blocks to fill the chip with 256-row tiles; run the
-        // small-batch kernel on chunks of 64 tokens instead
-        e = hipSuccess;
-        for (int m0 = 0; m0 < Mi && e == hipSuccess; m0 += 64) {
-            const int mc = Mi - m0 < 64 ? Mi - m0 : 64;
-            const uint16_t *xc = x + static_cast<size_t>(m0) * s.K;
-            void *yc = static_cast<char *>(y) + static_cast<size_t>(m0) * s.N * (f16 ? 2 : 4);
-            e = launch_small(records, xc, yc, mc, s, f16, stream);
-        }
     } else {
-        // many row tiles: two per item share one set of activation operands
-        e = launch_small(records, x, y, Mi, s, f16, stream);
+        const Route r = choose_route(s, Mi, fuse_planes);
+        if (r.path == PTQTP_ROUTE_TILE) {
+            if (r.second_kind < 0) {
+                e = launch_tile_kind(r.kind, fuse_planes, records, x, y, Mi, s, f16, stream, 0, -1);
+            } else {
+                e = launch_tile_kind(r.kind, fuse_planes, records, x, y, Mi, s, f16, stream, 0, r.split_row_tile);
+                if (e == hipSuccess)
+                    e = launch_tile_kind(r.second_kind, fuse_planes, records, x, y, Mi, s, f16, stream, r.split_row_tile, -1);
+            }
+        } else if (r.path == PTQTP_ROUTE_SMALL_CHUNKS) {
+            // the small-batch kernel on chunks of 64 tokens
+            e = hipSuccess;
+            for (int m0 = 0; m0 < Mi && e == hipSuccess; m0 += 64) {
+                const int mc = Mi - m0 < 64 ? Mi - m0 : 64;
+                const uint16_t *xc = x + static_cast<size_t>(m0) * s.K;
+                void *yc = static_cast<char *>(y) + static_cast<size_t>(m0) * s.N * (f16 ? 2 : 4);
+                e = launch_small(records, xc, yc, mc, s, f16, stream);
+            }
+        } else {
+            e = launch_small(records, x, y, Mi, s, f16, stream);
+        }
     }
     return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
@@ -1452,6 +1471,19 @@ ptqtp_status ptqtp_gemm(const void *packed, const uint16_t *x, void *y, int32_t 
 {
     const bool fuse = (y_dtype & PTQTP_FUSED_PLANES) != 0 && M >= 256;
     return run_forward(packed, x, y, y_dtype & ~PTQTP_FUSED_PLANES, M, N, K, group, stream, PTQTP_GEMM_MAX_M, fuse);
+}
+
+ptqtp_status ptqtp_gemm_route(int64_t M, int64_t N, int64_t K, int32_t group, int32_t y_dtype, int32_t *route)
+{
+    Shape s;
+    ptqtp_status st;
+    if (!route) return PTQTP_ERR_NULL;
+    if (!make_shape(M, N, K, group, &s, &st)) return st;
+    if (M > PTQTP_GEMM_MAX_M) return PTQTP_ERR_SHAPE;
+    if (M == 1) { route[0] = PTQTP_ROUTE_STREAM; route[1] = -1; route[2] = 0; route[3] = -1; return PTQTP_OK; }
+    const Route r = choose_route(s, static_cast<int>(M), (y_dtype & PTQTP_FUSED_PLANES) != 0 && M >= 256);
+    route[0] = r.path; route[1] = r.kind; route[2] = r.split_row_tile; route[3] = r.second_kind;
+    return PTQTP_OK;
 }
 
 static ptqtp_status plan_items(const ptqtp_linear *linears, int32_t count, int32_t group, int64_t *total) {

@@ -31,7 +31,7 @@ def test_header_symbols_exported(lib):
             "ptqtp_workspace_bytes", "ptqtp_status_string", "ptqtp_version", "ptqtp_tune", "ptqtp_gemm",
             "ptqtp_gemv_batch", "ptqtp_gemv_batch_plan", "ptqtp_batch_items", "ptqtp_batch_plan_bytes",
             "ptqtp_quantize", "ptqtp_quantize_workspace_bytes", "ptqtp_gemm_batch", "ptqtp_chain_plan_bytes",
-            "ptqtp_chain_plan", "ptqtp_chain_run", "ptqtp_chain_run_batch"} <= set(names)
+            "ptqtp_chain_plan", "ptqtp_chain_run", "ptqtp_chain_run_batch", "ptqtp_gemm_route"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in ptqtp.h but not exported"
 
@@ -189,3 +189,63 @@ def test_argument_validation_without_launch(lib):
     assert lib.ptqtp_tune(b"stream_waves", 17) == 2
     assert lib.ptqtp_tune(b"stream_waves", 0) == 0
     assert lib.ptqtp_tune(b"nonsense", 1) == 2
+
+
+# ---------------------------------------------------------------- which kernels a shape gets (host logic)
+def _route(lib, M, N, K, y_dtype=0):
+    r = (ctypes.c_int32 * 4)()
+    assert lib.ptqtp_gemm_route(M, N, K, 128, y_dtype, r) == 0
+    return tuple(r)
+
+
+def test_gemm_route_regimes(lib):
+    STREAM, SMALL, CHUNKS, TILE = 0, 1, 2, 3
+    assert _route(lib, 1, 4096, 4096)[0] == STREAM
+    # few tokens, or few rows: the small-batch kernel (in chunks of 64 tokens above 64)
+    for M in (2, 16, 32):
+        assert _route(lib, M, 14336, 4096)[0] == SMALL
+    assert _route(lib, 64, 4096, 4096)[0] == SMALL
+    assert _route(lib, 96, 4096, 4096)[0] == CHUNKS
+    assert _route(lib, 64, 328, 2304)[0] == SMALL
+    # a wide layer fills the chip with 64 x 64 tiles from a few dozen tokens on
+    assert _route(lib, 64, 14336, 4096) == (TILE, 4, 0, -1)
+    assert _route(lib, 128, 14336, 4096)[:2] == (TILE, 3)
+    # short prompts on 8B shapes: the smaller tiles; long ones: the big tiles
+    assert _route(lib, 256, 4096, 4096) == (TILE, 4, 0, -1)
+    assert _route(lib, 512, 4096, 4096) == (TILE, 3, 0, -1)
+    assert _route(lib, 512, 1024, 4096) == (TILE, 4, 0, -1)
+    assert _route(lib, 2048, 1024, 8192)[1] in (3, 4)
+    assert _route(lib, 2048, 8192, 28672)[1] in (0, 1, 2)
+    # 70B gate at 2048 tokens: 896 tiles of 256 x 256 = 3.5 rounds of 256 CUs -> three whole rounds, then smaller tiles
+    path, kind, split, second = _route(lib, 2048, 28672, 8192)
+    assert (path, kind) == (TILE, 0) and split == 96 * 16 and second in (1, 2, 3)
+    # every tile launch covers whole row blocks of its own tile: the split is a multiple of 16 row tiles
+    for M in (256, 300, 777, 2048, 5000):
+        for N in (1000, 4096, 9216, 28672):
+            r = _route(lib, M, N, 4096)
+            assert r[0] == TILE and 0 <= r[1] <= 4 and r[2] % 16 == 0 and r[2] < (N + 15) // 16
+            assert (r[2] == 0) == (r[3] == -1)
+    # the fused-plane flag only counts from 256 tokens on, and never changes the regime
+    assert _route(lib, 64, 4096, 4096, 16) == _route(lib, 64, 4096, 4096)
+    assert _route(lib, 512, 4096, 4096, 16)[0] == TILE
+
+
+def test_gemm_route_follows_tuning_and_rejects_bad_shapes(lib):
+    r = (ctypes.c_int32 * 4)()
+    try:
+        assert lib.ptqtp_tune(b"tile", 1) == 0
+        assert _route(lib, 2, 328, 2304)[0] == 3
+        assert lib.ptqtp_tune(b"tile", -1) == 0
+        assert _route(lib, 64, 14336, 4096)[0] == 1 and _route(lib, 200, 14336, 4096)[0] == 2
+        assert lib.ptqtp_tune(b"tile", 0) == 0
+        for variant, kind in ((1, 1), (2, 2), (3, 0), (4, 3), (5, 4)):
+            assert lib.ptqtp_tune(b"tile_variant", variant) == 0
+            assert _route(lib, 512, 4096, 4096) == (3, kind, 0, -1)
+        assert lib.ptqtp_tune(b"tile_variant", 6) == 2
+    finally:
+        lib.ptqtp_tune(b"tile", 0)
+        lib.ptqtp_tune(b"tile_variant", 0)
+    assert lib.ptqtp_gemm_route(4, 4096, 4096, 128, 0, None) == 1
+    assert lib.ptqtp_gemm_route(4, 4096, 4000, 128, 0, r) == 2
+    assert lib.ptqtp_gemm_route(4, 4096, 4096, 64, 0, r) == 3
+    assert lib.ptqtp_gemm_route(0, 4096, 4096, 128, 0, r) == 2
