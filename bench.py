@@ -303,6 +303,15 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
                     flag = ptq.PTQTP_F32 | ptq.PTQTP_FUSED_PLANES
                     us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blob, x, n, k, out=y, y_dtype=flag) for _ in range(4)], 4, reps=min(reps, 5))
                     res["70b"][f"{name}_{n}x{k}_M{M}_fused_planes"] = {"us": round(us, 2), "TFLOPs_counted_as_two_planes": round(4.0 * M * n * k / us / 1e6, 1)}
+            if name == "down" and not quick:
+                # longer prompts on the largest shape
+                for M in (4096, 8192):
+                    x = torch.randn(M, k, device=dev).half()
+                    y = torch.empty(M, n, device=dev)
+                    for flag, tag in ((ptq.PTQTP_F32, ""), (ptq.PTQTP_F32 | ptq.PTQTP_FUSED_PLANES, "_fused_planes")):
+                        us = _graph_time(torch, stream, lambda: [ptq.ptqtp_gemm(blob, x, n, k, out=y, y_dtype=flag) for _ in range(2)], 2, reps=3)
+                        res["70b"][f"{name}_{n}x{k}_M{M}{tag}"] = {"us": round(us, 1), "TFLOPs_counted_as_two_planes": round(4.0 * M * n * k / us / 1e6, 1)}
+                    del x, y
             del blob
             note(f"70B {name} done")
         # config 2 on the whole stack: one batched launch per step, M tokens per linear

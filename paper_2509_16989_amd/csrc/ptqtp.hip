@@ -713,8 +713,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
 //  - record words are fetched per scale group, 8 bytes per lane, plane and row tile.
 // FUSE as in gemm_tile_kernel.
 constexpr int kTile3Tokens = 256;
-constexpr int kTile3Chunk = 1040;                             // 1 KiB + 16-byte skew
-constexpr int kTile3BufBytes = 64 * kTile3Chunk;              // one 128-column group of 256 tokens
+constexpr int kTile3BufBytes = 64 * kTileChunk;              // one 128-column group of 256 tokens
 
 template <bool FUSE>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -745,7 +744,7 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
             asm volatile("" : "+v"(m));              // recompute the row address here: eight hoisted 64-bit addresses would not fit
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void *)(xcol + static_cast<size_t>(m) * K + g * 128),
-                (__attribute__((address_space(3))) void *)(xt + buf * kTile3BufBytes + ((w >> 1) * 16 + (w & 1) * 8 + j) * kTile3Chunk),
+                (__attribute__((address_space(3))) void *)(xt + buf * kTile3BufBytes + ((w >> 1) * 16 + (w & 1) * 8 + j) * kTileChunk),
                 16, 0, 0);
         }
     };
@@ -776,7 +775,7 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
     };
     auto compute = [&](const uintx2 (&pw)[4][2], const uintx2 (&sc)[4], int g) {
         // token tile mt of this wave: 64-token block 2*wm + mt/4, tokens (mt%4)*16 + nl -> chunk nl, run mt%4
-        const char *xb = xt + (g & 1) * kTile3BufBytes + wm * (32 * kTile3Chunk) + nl * kTile3Chunk + q * 16;
+        const char *xb = xt + (g & 1) * kTile3BufBytes + wm * (32 * kTileChunk) + nl * kTileChunk + q * 16;
         const int h = g & 1;
         constexpr int NPL = FUSE ? 1 : 2;
         half8 al[4][2];
@@ -799,7 +798,7 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
                 const half8 a = __builtin_bit_cast(
-                    half8, *reinterpret_cast<const uintx4 *>(xb + (mt >> 2) * (16 * kTile3Chunk) + (mt & 3) * 256 + fm * 64));
+                    half8, *reinterpret_cast<const uintx4 *>(xb + (mt >> 2) * (16 * kTileChunk) + (mt & 3) * 256 + fm * 64));
 #pragma unroll
                 for (int pl = 0; pl < NPL; ++pl)
 #pragma unroll
