@@ -526,6 +526,40 @@ def test_gemm_short_prompt_8b_sampled(ptq, name, M, flag):
     assert np.all(np.abs(got - ref) <= 3e-5 * B), f"{(np.abs(got - ref) / B).max():.3e}"
 
 
+def test_gemm_maximum_tokens_sampled(ptq):
+    # the largest M the entry point takes (65536 tokens), on a narrow layer; M + 1 is refused
+    N, K, M = 80, 384, 65536
+    lin = workloads.make_linear(N, K, 78)
+    x = workloads.make_x(M, K, 78)
+    packed = pack(ptq, lin)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    ptq.ptqtp_gemm(packed, dev(x), N, K, out=y)
+    assert bool(torch.isfinite(y).all())
+    toks = np.unique(np.concatenate([[0, 255, 256, 32767, 32768, M - 257, M - 256, M - 1], np.random.default_rng(16).integers(0, M, 200)]))
+    ref, B = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x[toks], threads=8)
+    got = y.cpu().numpy().astype(np.float64)[toks]
+    assert np.all(np.abs(got - ref) <= TIGHT * B)
+    with pytest.raises(ptq.PtqtpError):
+        ptq.ptqtp_gemm(packed, torch.zeros((M + 1, K), dtype=torch.float16, device="cuda:0"), N, K)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
+def test_gemm_tile_fp16_output_and_guard(ptq, variant):
+    # ragged rows and tokens on every tile: nothing is written outside y, fp16 output rounds once
+    N, K, M = 1000, 640, 300
+    lin = workloads.make_linear(N, K, 79)
+    x = workloads.make_x(M, K, 79)
+    buf = torch.full((M * N + 512,), 7.0, dtype=torch.float16, device="cuda:0")
+    out = buf[256:256 + M * N].view(M, N)
+    try:
+        ptq.ptqtp_tune("tile_variant", variant)
+        ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=ptq.PTQTP_F16, out=out)
+    finally:
+        ptq.ptqtp_tune("tile_variant", 0)
+    check(out, lin, x, tight=TIGHT_F16)
+    assert (buf[:256] == 7).all() and (buf[256 + M * N:] == 7).all()
+
+
 def test_gemm_small_rows_match_gemv(ptq):
     # each token of a batch gets the bits batch-1 would give it? not required (different
     # reduction trees are both correct) -- but both must sit inside the tight gate
