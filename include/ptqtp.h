@@ -210,9 +210,11 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
  *   ptqtp_chain_run    runs the chain: one launch per level, in stream order (capture it in a
  *                      HIP graph to replay a decode step); a level with few work items gets more
  *                      waves per item.  `stages`, `count` must be the ones the plan was written from.
- *   ptqtp_chain_run_batch  the same chain at M tokens, 1 <= M <= PTQTP_GEMM_SMALL_MAX_M: every x is then
+ *   ptqtp_chain_run_batch  the same chain at M tokens, 1 <= M <= PTQTP_GEMM_MAX_M: every x is then
  *                      fp16 [M, K] row-major, every y and residual [M, N] (or [M, N/2]) row-major.  One
- *                      launch of the small-batch kernel per stage, in array order; needs no plan.
+ *                      launch per stage, in array order: the small-batch kernel up to
+ *                      PTQTP_GEMM_SMALL_MAX_M tokens, an MFMA tile with the epilogue in its store above
+ *                      (a prompt through the same chain); needs no plan.
  * ptqtp_chain_plan_bytes returns 0 for invalid arguments.
  */
 enum { PTQTP_EPI_NONE = 0, PTQTP_EPI_SWIGLU = 1 };

@@ -520,6 +520,55 @@ gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict
 // share its L2 copy of the packed rows.
 constexpr int kTileChunk = 1040;                    // 1 KiB chunk of four tokens + 16-byte skew (tiles with direct-to-LDS loads)
 
+// Epilogues of the MFMA tiles (the decode chain at many tokens): `gated` = the layer stacks N/2 gate rows over N/2
+// up rows and a wave's row tiles alternate gate, up of the same 16 outputs: out = silu(gate) * up; then, if
+// residual != null, out += residual[m][n] (fp16, same shape as the output).
+struct TileEpilogue {
+    const uint16_t *residual;
+    int gated;
+};
+
+// The r-th row tile of a wave whose first tile (or gate/up pair) index is `first`, out of RT row tiles
+__device__ __forceinline__ int tile_row(int first, int r, int RT, int gated) {
+    if (!gated) return first + r;
+    const int P = RT >> 1;
+    const int p = first + (r >> 1);
+    return (p < P ? p : P - 1) + (r & 1) * P;
+}
+
+// Store one wave's accumulators: acc[r][mt] = rows of row tile r (lane nl) x tokens m_of(mt, j)
+template <int RTW, int MTW, typename TokenOf>
+__device__ __forceinline__ void tile_store(const floatx4 (&acc)[RTW][MTW], void *y, int y_f16, int first, int nl, int M, int N,
+                                           const TileEpilogue &ep, TokenOf m_of)
+{
+    const int n_out = ep.gated ? N >> 1 : N;
+#pragma unroll
+    for (int r = 0; r < RTW; ++r) {
+        if (ep.gated && (r & 1)) continue;
+        const int t = ep.gated ? first + (r >> 1) : first + r;       // output tile
+        const int n = t * kTileRows + nl;
+        if (n < n_out) {
+#pragma unroll
+            for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int m = m_of(mt, j);
+                    if (m < M) {
+                        float out = acc[r][mt][j];
+                        if (ep.gated) {
+                            const float up = acc[r + 1 < RTW ? r + 1 : r][mt][j];
+                            out = (out / (1.0f + __expf(-out))) * up;             // silu(gate) * up
+                        }
+                        const size_t off = static_cast<size_t>(m) * n_out + n;
+                        if (ep.residual != nullptr) out += half_bits_to_float(load_global<uint16_t>(ep.residual + off));
+                        if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(out);
+                        else reinterpret_cast<float *>(y)[off] = out;
+                    }
+                }
+        }
+    }
+}
+
 __device__ __forceinline__ half8 decode8(uint32_t word, int parity) {
     const uint32_t fp4 = (parity ? (word << 1) : word) & 0xAAAAAAAAu;
     const half2v h0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(fp4, 1.0f, 0);
@@ -545,7 +594,7 @@ struct TileRecs {               // the records of a wave's RTW row tiles for one
 template <int MTW, bool FUSE, int RTW>
 __global__ void __launch_bounds__(256)
 gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
-                 int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB, int nb0)
+                 int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB, int nb0, TileEpilogue ep)
 {
     extern __shared__ char xt[];                     // [2][TM/4 chunks][kTileChunk]
     constexpr int TM = 16 * MTW, NRT = 4 * RTW;      // tokens, row tiles per workgroup
@@ -557,7 +606,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     const int nb = nb0 + (slot / MB) * 8 + xcd, mb = slot % MB;   // this launch covers row blocks nb0 .. NB-1
     if (nb >= NB) return;                            // whole workgroup, before any barrier
     const int m0 = mb * TM;
-    const int rt_base = nb * NRT + w * RTW;
+    const int rt_base = ep.gated ? nb * (NRT / 2) + w * (RTW / 2) : nb * NRT + w * RTW;   // first tile, or first pair
     const int NG = K / 128;
 
     // staging (global -> LDS directly): wave w brings in chunks w, w+4, ... of the group; a chunk is the 256-byte group
@@ -581,7 +630,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     const uint8_t *rec[RTW];
 #pragma unroll
     for (int r = 0; r < RTW; ++r) {
-        int rt = rt_base + r;
+        int rt = tile_row(rt_base, r, RT, ep.gated);
         rt = rt < RT ? rt : RT - 1;
         rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes;
     }
@@ -679,24 +728,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
         if (ks + 1 < KS) step(rb, ra, ks + 1);
     }
 
-#pragma unroll
-    for (int r = 0; r < RTW; ++r) {
-        const int rt = rt_base + r;
-        const int n = rt * kTileRows + nl;
-        if (rt < RT && n < N) {
-#pragma unroll
-            for (int mt = 0; mt < MTW; ++mt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int m = m0 + mt * 16 + 4 * q + j;
-                    if (m < M) {
-                        const size_t off = static_cast<size_t>(m) * N + n;
-                        if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(acc[r][mt][j]);
-                        else reinterpret_cast<float *>(y)[off] = acc[r][mt][j];
-                    }
-                }
-        }
-    }
+    tile_store<RTW, MTW>(acc, y, y_f16, rt_base, nl, M, N, ep, [&](int mt, int j) { return m0 + mt * 16 + 4 * q + j; });
 }
 
 // Large prefill tile: workgroup = 4 x 2 waves (two per SIMD), each 4 row tiles x 8 token tiles:
@@ -718,7 +750,7 @@ constexpr int kTile3BufBytes = 64 * kTileChunk;              // one 128-column g
 template <bool FUSE>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
-                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB, int nb0)
+                  int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB, int nb0, TileEpilogue ep)
 {
     extern __shared__ char xt[];                     // [2][64 chunks][1040]
     constexpr int TM = kTile3Tokens, NRT = 16;
@@ -730,7 +762,7 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
     const int nb = nb0 + (slot / MB) * 8 + xcd, mb = slot % MB;   // this launch covers row blocks nb0 .. NB-1
     if (nb >= NB) return;                            // whole workgroup, before any barrier
     const int m0 = mb * TM;
-    const int rt_base = nb * NRT + wn * 4;
+    const int rt_base = ep.gated ? nb * (NRT / 2) + wn * 2 : nb * NRT + wn * 4;   // first tile, or first pair
     const int NG = K / 128;
 
     // staging role: wave w brings in chunks 8*(w%2) .. +7 of 64-token block w/2; lane t*16+p: piece p of token c + 16*t
@@ -752,7 +784,7 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
     const uint8_t *rec[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        int rt = rt_base + r;
+        int rt = tile_row(rt_base, r, RT, ep.gated);
         rt = rt < RT ? rt : RT - 1;
         rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes + lane * 16;
     }
@@ -831,32 +863,16 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
         }
     }
 
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int rt = rt_base + r;
-        const int n = rt * kTileRows + nl;
-        if (rt < RT && n < N) {
-#pragma unroll
-            for (int mt = 0; mt < 8; ++mt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int m = m0 + wm * 128 + mt * 16 + 4 * q + j;
-                    if (m < M) {
-                        const size_t off = static_cast<size_t>(m) * N + n;
-                        if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(acc[r][mt][j]);
-                        else reinterpret_cast<float *>(y)[off] = acc[r][mt][j];
-                    }
-                }
-        }
-    }
+    tile_store<4, 8>(acc, y, y_f16, rt_base, nl, M, N, ep, [&](int mt, int j) { return m0 + wm * 128 + mt * 16 + 4 * q + j; });
 }
 
 template <bool FUSE>
 hipError_t launch_gemm_tile3(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
-                             hipStream_t stream, int nb0 = 0, int nb1 = -1)
+                             hipStream_t stream, int nb0 = 0, int nb1 = -1, TileEpilogue ep = {nullptr, 0})
 {
     const int MB = (M + kTile3Tokens - 1) / kTile3Tokens;
-    const int NB = nb1 >= 0 ? nb1 : static_cast<int>((s.RT + 15) / 16);
+    const int64_t units = ep.gated ? s.RT / 2 : s.RT, per = ep.gated ? 8 : 16;   // pairs per workgroup when gated
+    const int NB = nb1 >= 0 ? nb1 : static_cast<int>((units + per - 1) / per);
     const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
     const size_t lds = 2 * static_cast<size_t>(kTile3BufBytes);
     static bool configured = false;                  // raise the dynamic LDS limit once per process
@@ -868,18 +884,20 @@ hipError_t launch_gemm_tile3(const uint8_t *records, const uint16_t *x, void *y,
     }
     hipLaunchKernelGGL((gemm_tile3_kernel<FUSE>), dim3(static_cast<unsigned>(grid)), dim3(512), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
-                       static_cast<int>(s.KS), y_f16, MB, NB, nb0);
+                       static_cast<int>(s.KS), y_f16, MB, NB, nb0, ep);
     return hipGetLastError();
 }
 
 // row blocks (of 64*RTW rows) nb0 .. nb1-1; nb1 < 0: to the end
 template <int MTW, bool FUSE, int RTW = 4>
 hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
-                            hipStream_t stream, int nb0 = 0, int nb1 = -1)
+                            hipStream_t stream, int nb0 = 0, int nb1 = -1, TileEpilogue ep = {nullptr, 0})
 {
     constexpr int TM = 16 * MTW, NRT = 4 * RTW;
+    if (ep.gated && RTW < 2) return hipErrorInvalidValue;   // a wave needs a gate tile and its up tile
     const int MB = (M + TM - 1) / TM;
-    const int NB = nb1 >= 0 ? nb1 : static_cast<int>((s.RT + NRT - 1) / NRT);
+    const int64_t units = ep.gated ? s.RT / 2 : s.RT, per = ep.gated ? NRT / 2 : NRT;
+    const int NB = nb1 >= 0 ? nb1 : static_cast<int>((units + per - 1) / per);
     const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
     const size_t lds = 2 * static_cast<size_t>(TM / 4) * kTileChunk;
     static bool configured = false;                  // raise the dynamic LDS limit once per process
@@ -891,7 +909,7 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     }
     hipLaunchKernelGGL((gemm_tile_kernel<MTW, FUSE, RTW>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
-                       static_cast<int>(s.KS), y_f16, MB, NB, nb0);
+                       static_cast<int>(s.KS), y_f16, MB, NB, nb0, ep);
     return hipGetLastError();
 }
 
@@ -945,16 +963,16 @@ double small_cost(int row_tiles, int groups, int M)
 
 // Launch tile kind k over row tiles rt0 .. rt1-1 (rt0 a multiple of 16; rt1 < 0: to the end, else a multiple of 16).
 hipError_t launch_tile_kind(int k, bool fuse, const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s,
-                            int y_f16, hipStream_t stream, int rt0, int rt1)
+                            int y_f16, hipStream_t stream, int rt0, int rt1, TileEpilogue ep = {nullptr, 0})
 {
     const int per = kTileKinds[k].row_tiles;
     const int nb0 = rt0 / per, nb1 = rt1 < 0 ? -1 : rt1 / per;
 #define PTQTP_TILE(MTW_, RTW_)                                                                         \
-    (fuse ? launch_gemm_tile<MTW_, true, RTW_>(records, x, y, M, s, y_f16, stream, nb0, nb1)           \
-          : launch_gemm_tile<MTW_, false, RTW_>(records, x, y, M, s, y_f16, stream, nb0, nb1))
+    (fuse ? launch_gemm_tile<MTW_, true, RTW_>(records, x, y, M, s, y_f16, stream, nb0, nb1, ep)       \
+          : launch_gemm_tile<MTW_, false, RTW_>(records, x, y, M, s, y_f16, stream, nb0, nb1, ep))
     switch (k) {
-        case 0: return fuse ? launch_gemm_tile3<true>(records, x, y, M, s, y_f16, stream, nb0, nb1)
-                            : launch_gemm_tile3<false>(records, x, y, M, s, y_f16, stream, nb0, nb1);
+        case 0: return fuse ? launch_gemm_tile3<true>(records, x, y, M, s, y_f16, stream, nb0, nb1, ep)
+                            : launch_gemm_tile3<false>(records, x, y, M, s, y_f16, stream, nb0, nb1, ep);
         case 1: return PTQTP_TILE(8, 4);
         case 2: return PTQTP_TILE(8, 2);
         case 3: return PTQTP_TILE(4, 2);
@@ -1274,6 +1292,23 @@ hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int 
 // one stage of a decode chain at 1..64 tokens (called from ptqtp_chain.hip): the small-batch item kernel with the
 // stage's epilogue in its final reduction
 namespace ptqtp_detail {
+// One chain stage at many tokens on the cheapest single MFMA tile launch (a gated stage needs two row tiles per wave)
+hipError_t tile_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M, int64_t N,
+                      int64_t K, int y_f16, int gated, hipStream_t stream)
+{
+    Shape s;
+    s.N = N; s.K = K; s.NG = K / 128;
+    s.RT = (N + kTileRows - 1) / kTileRows;
+    s.KS = (K + kStepK - 1) / kStepK;
+    int best = 1;
+    double cost = 1e30;
+    for (int k = 0; k < (gated ? kTileKindCount - 1 : kTileKindCount); ++k) {
+        const double c = tile_cost(k, 0, static_cast<int>(s.RT), M);
+        if (c < cost) { cost = c; best = k; }
+    }
+    return launch_tile_kind(best, false, records, x, y, M, s, y_f16, stream, 0, -1, TileEpilogue{residual, gated});
+}
+
 hipError_t small_batch_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M,
                              int64_t N, int64_t K, int y_f16, int gated, hipStream_t stream)
 {

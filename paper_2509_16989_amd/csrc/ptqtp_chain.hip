@@ -19,6 +19,9 @@ int g_chain_waves = 0, g_chain_depth = 0;      // ptqtp_tune("chain_waves" / "ch
 // ptqtp.hip: the small-batch item kernel with a stage's epilogue in its final reduction
 hipError_t small_batch_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M,
                              int64_t N, int64_t K, int y_f16, int gated, hipStream_t stream);
+// ptqtp.hip: one MFMA tile launch with the epilogue in its store (more than 64 tokens)
+hipError_t tile_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M,
+                      int64_t N, int64_t K, int y_f16, int gated, hipStream_t stream);
 }
 
 namespace {
@@ -311,11 +314,13 @@ ptqtp_status ptqtp_chain_run(const ptqtp_stage *stages, int32_t count, int32_t g
 ptqtp_status ptqtp_chain_run_batch(const ptqtp_stage *stages, int32_t count, int32_t group, int64_t M, void *stream_) {
     int n_levels; int64_t total; ptqtp_status st;
     if (!chain_geometry(stages, count, group, nullptr, nullptr, &n_levels, &total, &st)) return st;
-    if (M < 1 || M > PTQTP_GEMM_SMALL_MAX_M) return PTQTP_ERR_SHAPE;
+    if (M < 1 || M > PTQTP_GEMM_MAX_M) return PTQTP_ERR_SHAPE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     for (int i = 0; i < count; ++i) {
         const ptqtp_stage &s = stages[i];
-        const hipError_t e = ptqtp_detail::small_batch_stage(
+        // up to 64 tokens: the small-batch kernel; above: one MFMA tile launch with the epilogue in its store
+        const auto run = M <= PTQTP_GEMM_SMALL_MAX_M ? ptqtp_detail::small_batch_stage : ptqtp_detail::tile_stage;
+        const hipError_t e = run(
             static_cast<const uint8_t *>(s.packed) + kHeaderBytes, s.x, s.y, s.residual, static_cast<int>(M), s.N, s.K,
             s.y_dtype == PTQTP_F16, s.epilogue == PTQTP_EPI_SWIGLU, stream);
         if (e != hipSuccess) return PTQTP_ERR_HIP;

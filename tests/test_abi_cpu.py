@@ -117,7 +117,7 @@ def test_chain_plan_validation(lib):
     assert lib.ptqtp_chain_run(arr, 3, 128, None, None) == 1
     assert lib.ptqtp_chain_run(arr, 3, 128, ctypes.c_void_p(0x100010), None) == 6
     assert lib.ptqtp_chain_run_batch(arr, 3, 128, 0, None) == 2
-    assert lib.ptqtp_chain_run_batch(arr, 3, 128, 65, None) == 2
+    assert lib.ptqtp_chain_run_batch(arr, 3, 128, 65537, None) == 2
     assert lib.ptqtp_chain_run_batch(None, 3, 128, 4, None) == 1
     arr[1].N = 944
     assert lib.ptqtp_chain_run(arr, 3, 128, fake, None) == 2

@@ -206,7 +206,41 @@ def build_stack_batch(ptq, layers, H, KV, I, M, seed):
     return lins, stages, bufs
 
 
-@pytest.mark.parametrize("M", [5, 33])
+@pytest.mark.parametrize("M", [65, 130, 256, 300])
+@pytest.mark.parametrize("N,K,epi,res,ydt", [
+    (200, 640, "none", True, torch.float16), (1024, 1024, "none", False, torch.float32),
+    (960, 384, "swiglu", False, torch.float16), (2048, 1024, "swiglu", True, torch.float32), (64, 128, "swiglu", True, torch.float16),
+    (8192, 256, "swiglu", True, torch.float16), (9216, 256, "none", True, torch.float16),
+])
+def test_chain_batch_single_stage_on_tiles(ptq, M, N, K, epi, res, ydt):
+    # more than 64 tokens: an MFMA tile with the epilogue in its store (a gated stage pairs gate and up tiles per wave)
+    lin = workloads.make_linear(N, K, 87, N, K)
+    x = workloads.make_x(M, K, 87, N, M)
+    n_out = N // 2 if epi == "swiglu" else N
+    r = workloads.make_x(M, n_out, 87, N, M, 7) if res else None
+    y = torch.full((M, n_out), float("nan"), dtype=ydt, device="cuda:0")
+    plan = ptq.ptqtp_chain_plan([dict(packed=pack(ptq, lin), x=dev(x), y=y, N=N, K=K, level=0,
+                                      residual=dev(r) if res else None,
+                                      epilogue=ptq.PTQTP_EPI_SWIGLU if epi == "swiglu" else ptq.PTQTP_EPI_NONE)])
+    ptq.ptqtp_chain_run_batch(plan, M)
+    torch.cuda.synchronize()
+    check_stage(y, lin, x, epi, r)
+
+
+def test_chain_batch_in_place_residual_on_tiles(ptq):
+    # y may be the stage's own residual buffer (the residual stream updated in place)
+    N, K, M = 512, 384, 200
+    lin = workloads.make_linear(N, K, 88)
+    x = workloads.make_x(M, K, 88)
+    r = workloads.make_x(M, N, 88, 7)
+    buf = dev(r).clone()
+    plan = ptq.ptqtp_chain_plan([dict(packed=pack(ptq, lin), x=dev(x), y=buf, N=N, K=K, level=0, residual=buf)])
+    ptq.ptqtp_chain_run_batch(plan, M)
+    torch.cuda.synchronize()
+    check_stage(buf, lin, x, "none", r)
+
+
+@pytest.mark.parametrize("M", [5, 33, 150])
 def test_chain_batch_dependent_stack(ptq, M):
     # with M tokens a row of qkv's output is not contiguous with the next token's q part, so o gets its input through
     # a copy the test makes between two runs of sub-chains (stands in for attention); every stage is checked on its real input
