@@ -408,7 +408,7 @@ def dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream, quick=False):
     # the same chain at 16 tokens per stage and for a 512-token prompt (ptqtp_chain_run_batch); o reads a buffer of its
     # own there (with several tokens the q part of qkv's output is not a contiguous [M, K] matrix), the launches stay
     # in stream order
-    def chain_at(M, steps, warmup):
+    def chain_at(M, steps, warmup, fused=False):
         stages_m, prev = [], None
         for i, st in enumerate(stages):
             n_out = st["N"] // 2 if st["epilogue"] == ptq.PTQTP_EPI_SWIGLU else st["N"]
@@ -416,7 +416,7 @@ def dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream, quick=False):
             xm = (torch.randn(M, st["K"], device=dev) * 0.5).half() if i % 4 == 1 or prev is None else prev
             resid = None if st["residual"] is None else torch.zeros((M, n_out), dtype=torch.float16, device=dev)
             stages_m.append(dict(packed=st["packed"], x=xm, y=ym, N=st["N"], K=st["K"], level=st["level"], residual=resid,
-                                 epilogue=st["epilogue"]))
+                                 epilogue=st["epilogue"], fused_planes=fused))
             prev = ym
         plan_m = ptq.ptqtp_chain_plan(stages_m)
         ptq.ptqtp_chain_run_batch(plan_m, M)
@@ -428,6 +428,7 @@ def dependent_chain_timing(ptq, torch, blobs, jobs, dims, stream, quick=False):
 
     out["M16_us_per_step"] = round(chain_at(16, 5 if quick else 50, 2 if quick else 10) * 1e3, 1)
     out["M512_us_per_step"] = round(chain_at(512, 3 if quick else 10, 1 if quick else 3) * 1e3, 1)
+    out["M512_fused_planes_us_per_step"] = round(chain_at(512, 3 if quick else 10, 1 if quick else 3, fused=True) * 1e3, 1)
     return out
 
 

@@ -134,7 +134,8 @@ ptqtp_status ptqtp_gemm_small(const void *packed, const uint16_t *x, void *y, in
  * alpha*T (exact in fp16) to the matrix pipe.  Arguments as in ptqtp_gemm_small.
  */
 /*
- * PTQTP_FUSED_PLANES, OR-ed into y_dtype of ptqtp_gemm only: from 256 tokens on, rebuild the weight
+ * PTQTP_FUSED_PLANES, OR-ed into y_dtype of ptqtp_gemm (and of a ptqtp_stage, where it counts in
+ * ptqtp_chain_run_batch) only: from 256 tokens on, rebuild the weight
  * before the matrix pipe, w16 = fp16(alpha1*t1 + alpha2*t2) -- ONE rounding per weight, both
  * products being exact in fp16 -- and run one MFMA pass over w16 instead of one per plane (the
  * "dequantization" forward Sec. "Inference Efficiency" names beside the dequantization-free one).

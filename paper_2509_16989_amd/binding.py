@@ -285,7 +285,8 @@ class ChainPlan:
 
 def ptqtp_chain_plan(stages, group: int = 128) -> ChainPlan:
     """stages: sequence of dicts with packed, x, y, N, K and optionally residual (tensor or None),
-    epilogue (PTQTP_EPI_*), level (int); y's torch dtype (float32 / float16) gives y_dtype."""
+    epilogue (PTQTP_EPI_*), level (int), fused_planes (bool: honoured by ptqtp_chain_run_batch from 256 tokens on);
+    y's torch dtype (float32 / float16) gives y_dtype."""
     n = len(stages)
     arr = (_Stage * max(n, 1))()
     keep = []
@@ -297,7 +298,8 @@ def ptqtp_chain_plan(stages, group: int = 128) -> ChainPlan:
         arr[i] = _Stage(_dev(s["packed"], torch.uint8, "packed"), _dev(s["x"], torch.float16, "x"), _dev(y, y.dtype, "y"),
                         _dev(res, torch.float16, "residual") if res is not None else None,
                         int(s["N"]), int(s["K"]), int(s.get("epilogue", PTQTP_EPI_NONE)),
-                        PTQTP_F32 if y.dtype == torch.float32 else PTQTP_F16, int(s.get("level", i)), 0)
+                        (PTQTP_F32 if y.dtype == torch.float32 else PTQTP_F16) | (PTQTP_FUSED_PLANES if s.get("fused_planes") else 0),
+                        int(s.get("level", i)), 0)
         keep += [s["packed"], s["x"], y, res]
     lib = _load()
     nbytes = int(lib.ptqtp_chain_plan_bytes(arr, n, group))

@@ -1294,7 +1294,7 @@ hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int 
 namespace ptqtp_detail {
 // One chain stage at many tokens on the cheapest single MFMA tile launch (a gated stage needs two row tiles per wave)
 hipError_t tile_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M, int64_t N,
-                      int64_t K, int y_f16, int gated, hipStream_t stream)
+                      int64_t K, int y_f16, int gated, bool fuse_planes, hipStream_t stream)
 {
     Shape s;
     s.N = N; s.K = K; s.NG = K / 128;
@@ -1303,10 +1303,10 @@ hipError_t tile_stage(const uint8_t *records, const uint16_t *x, void *y, const 
     int best = 1;
     double cost = 1e30;
     for (int k = 0; k < (gated ? kTileKindCount - 1 : kTileKindCount); ++k) {
-        const double c = tile_cost(k, 0, static_cast<int>(s.RT), M);
+        const double c = tile_cost(k, fuse_planes ? 1 : 0, static_cast<int>(s.RT), M);
         if (c < cost) { cost = c; best = k; }
     }
-    return launch_tile_kind(best, false, records, x, y, M, s, y_f16, stream, 0, -1, TileEpilogue{residual, gated});
+    return launch_tile_kind(best, fuse_planes, records, x, y, M, s, y_f16, stream, 0, -1, TileEpilogue{residual, gated});
 }
 
 hipError_t small_batch_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M,

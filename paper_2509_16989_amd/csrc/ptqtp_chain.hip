@@ -21,7 +21,7 @@ hipError_t small_batch_stage(const uint8_t *records, const uint16_t *x, void *y,
                              int64_t N, int64_t K, int y_f16, int gated, hipStream_t stream);
 // ptqtp.hip: one MFMA tile launch with the epilogue in its store (more than 64 tokens)
 hipError_t tile_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M,
-                      int64_t N, int64_t K, int y_f16, int gated, hipStream_t stream);
+                      int64_t N, int64_t K, int y_f16, int gated, bool fuse_planes, hipStream_t stream);
 }
 
 namespace {
@@ -206,7 +206,8 @@ bool chain_geometry(const ptqtp_stage *stages, int32_t count, int32_t group, Sta
         if (s.N <= 0 || s.K <= 0 || s.K % group != 0 || s.N > (1ll << 30) || s.K > (1ll << 30)) { *st = PTQTP_ERR_SHAPE; return false; }
         if (s.epilogue != PTQTP_EPI_NONE && s.epilogue != PTQTP_EPI_SWIGLU) { *st = PTQTP_ERR_SHAPE; return false; }
         if (s.epilogue == PTQTP_EPI_SWIGLU && s.N % 32 != 0) { *st = PTQTP_ERR_SHAPE; return false; }
-        if (s.y_dtype != PTQTP_F32 && s.y_dtype != PTQTP_F16) { *st = PTQTP_ERR_DTYPE; return false; }
+        const int32_t ydt = s.y_dtype & ~PTQTP_FUSED_PLANES;      // the flag only counts in ptqtp_chain_run_batch
+        if (ydt != PTQTP_F32 && ydt != PTQTP_F16) { *st = PTQTP_ERR_DTYPE; return false; }
         if (s.level < 0 || s.level < prev_level || s.reserved != 0) { *st = PTQTP_ERR_SHAPE; return false; }
         if ((reinterpret_cast<uintptr_t>(s.packed) & 255) || (reinterpret_cast<uintptr_t>(s.x) & 15) ||
             (reinterpret_cast<uintptr_t>(s.y) & 15) || (reinterpret_cast<uintptr_t>(s.residual) & 15)) {
@@ -229,7 +230,7 @@ bool chain_geometry(const ptqtp_stage *stages, int32_t count, int32_t group, Sta
             d.N = static_cast<int32_t>(s.N); d.K = static_cast<int32_t>(s.K);
             d.RT = static_cast<int32_t>(RT); d.KS = static_cast<int32_t>(KS);
             d.first_item = static_cast<int32_t>(item); d.items = static_cast<int32_t>(items);
-            d.epilogue = s.epilogue; d.y_f16 = s.y_dtype == PTQTP_F16;
+            d.epilogue = s.epilogue; d.y_f16 = ydt == PTQTP_F16;
             d.level = lv;
             descs[i] = d;
         }
@@ -319,10 +320,13 @@ ptqtp_status ptqtp_chain_run_batch(const ptqtp_stage *stages, int32_t count, int
     for (int i = 0; i < count; ++i) {
         const ptqtp_stage &s = stages[i];
         // up to 64 tokens: the small-batch kernel; above: one MFMA tile launch with the epilogue in its store
-        const auto run = M <= PTQTP_GEMM_SMALL_MAX_M ? ptqtp_detail::small_batch_stage : ptqtp_detail::tile_stage;
-        const hipError_t e = run(
-            static_cast<const uint8_t *>(s.packed) + kHeaderBytes, s.x, s.y, s.residual, static_cast<int>(M), s.N, s.K,
-            s.y_dtype == PTQTP_F16, s.epilogue == PTQTP_EPI_SWIGLU, stream);
+        const uint8_t *records = static_cast<const uint8_t *>(s.packed) + kHeaderBytes;
+        const int f16 = (s.y_dtype & ~PTQTP_FUSED_PLANES) == PTQTP_F16, gated = s.epilogue == PTQTP_EPI_SWIGLU;
+        const bool fuse = (s.y_dtype & PTQTP_FUSED_PLANES) != 0 && M >= 256;
+        const hipError_t e =
+            M <= PTQTP_GEMM_SMALL_MAX_M
+                ? ptqtp_detail::small_batch_stage(records, s.x, s.y, s.residual, static_cast<int>(M), s.N, s.K, f16, gated, stream)
+                : ptqtp_detail::tile_stage(records, s.x, s.y, s.residual, static_cast<int>(M), s.N, s.K, f16, gated, fuse, stream);
         if (e != hipSuccess) return PTQTP_ERR_HIP;
     }
     return PTQTP_OK;
