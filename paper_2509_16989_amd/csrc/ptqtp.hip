@@ -731,10 +731,11 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     tile_store<RTW, MTW>(acc, y, y_f16, rt_base, nl, M, N, ep, [&](int mt, int j) { return m0 + mt * 16 + 4 * q + j; });
 }
 
-// Large prefill tile: workgroup = 4 x 2 waves (two per SIMD), each 4 row tiles x 8 token tiles:
-// 256 rows x 256 tokens.  Twice the tokens per decoded trit of the 128-token tiles at the same
-// L1 traffic per MFMA, and a second wave on every SIMD to fill the issue slots the first one
-// leaves.  What makes it fit in 256 registers per lane:
+// Large prefill tile: 256 rows x 256 tokens, eight waves along the rows (two per SIMD), each 2 row tiles x all 16
+// token tiles: every trit of the workgroup is expanded exactly once and used for 16 MFMAs (a 4 x 2 arrangement of
+// waves with 4 row tiles x 8 token tiles each expands every trit twice and measured 3-9 % slower, although it reads
+// half as many operands from LDS), and a second wave on every SIMD fills the issue slots the first one leaves.
+// What makes it fit in 256 registers per lane:
 //  - activations go from global memory straight into LDS (global_load_lds_dwordx4, no staging
 //    registers).  One instruction moves a 1-KiB chunk = the 256 bytes (one 128-column group) of
 //    four tokens, lane t*16+p bringing 16-byte piece p of token t -- four full 256-byte runs, the
@@ -753,16 +754,15 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
                   int M, int N, int K, int RT, int KS, int y_f16, int MB, int NB, int nb0, TileEpilogue ep)
 {
     extern __shared__ char xt[];                     // [2][64 chunks][1040]
-    constexpr int TM = kTile3Tokens, NRT = 16;
+    constexpr int TM = kTile3Tokens, NRT = 16, RTW = 2, MTW = 16;   // row tiles, token tiles per wave
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nl = lane & 15, q = lane >> 4;
-    const int wm = w & 1, wn = w >> 1;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int nb = nb0 + (slot / MB) * 8 + xcd, mb = slot % MB;   // this launch covers row blocks nb0 .. NB-1
     if (nb >= NB) return;                            // whole workgroup, before any barrier
     const int m0 = mb * TM;
-    const int rt_base = ep.gated ? nb * (NRT / 2) + wn * 2 : nb * NRT + wn * 4;   // first tile, or first pair
+    const int rt_base = ep.gated ? nb * (NRT / 2) + w * (RTW / 2) : nb * NRT + w * RTW;   // first tile, or first pair
     const int NG = K / 128;
 
     // staging role: wave w brings in chunks 8*(w%2) .. +7 of 64-token block w/2; lane t*16+p: piece p of token c + 16*t
@@ -781,38 +781,38 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
         }
     };
 
-    const uint8_t *rec[4];
+    const uint8_t *rec[RTW];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < RTW; ++r) {
         int rt = tile_row(rt_base, r, RT, ep.gated);
         rt = rt < RT ? rt : RT - 1;
         rec[r] = records + static_cast<size_t>(rt) * KS * kRecordBytes + lane * 16;
     }
 
-    floatx4 acc[4][8];
+    floatx4 acc[RTW][MTW];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < RTW; ++r)
 #pragma unroll
-        for (int mt = 0; mt < 8; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < MTW; ++mt) acc[r][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // words of group g: record g/2, half g%2 -> 8 bytes per lane, plane and row tile; scales: 4 fp16 per row
-    auto load_group = [&](uintx2 (&pw)[4][2], uintx2 (&sc)[4], int g) {
+    auto load_group = [&](uintx2 (&pw)[RTW][2], uintx2 (&sc)[RTW], int g) {
         const size_t off = static_cast<size_t>(g >> 1) * kRecordBytes + (g & 1) * 8;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < RTW; ++r) {
             pw[r][0] = load_global<uintx2>(rec[r] + off);
             pw[r][1] = load_global<uintx2>(rec[r] + off + kPlaneBytes);
             sc[r] = load_global<uintx2>(rec[r] - lane * 16 + static_cast<size_t>(g >> 1) * kRecordBytes + 2 * kPlaneBytes + nl * 8);
         }
     };
-    auto compute = [&](const uintx2 (&pw)[4][2], const uintx2 (&sc)[4], int g) {
-        // token tile mt of this wave: 64-token block 2*wm + mt/4, tokens (mt%4)*16 + nl -> chunk nl, run mt%4
-        const char *xb = xt + (g & 1) * kTile3BufBytes + wm * (32 * kTileChunk) + nl * kTileChunk + q * 16;
+    auto compute = [&](const uintx2 (&pw)[RTW][2], const uintx2 (&sc)[RTW], int g) {
+        // token tile mt: 64-token block mt/4, tokens (mt%4)*16 + nl -> chunk nl, run mt%4
+        const char *xb = xt + (g & 1) * kTile3BufBytes + nl * kTileChunk + q * 16;
         const int h = g & 1;
         constexpr int NPL = FUSE ? 1 : 2;
-        half8 al[4][2];
+        half8 al[RTW][2];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < RTW; ++r) {
             const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].x >> 16) : (sc[r].x & 0xffffu)));
             const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h ? (sc[r].y >> 16) : (sc[r].y & 0xffffu)));
             al[r][0] = half8{a1, a1, a1, a1, a1, a1, a1, a1};
@@ -820,32 +820,32 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
         }
 #pragma unroll
         for (int fm = 0; fm < 4; ++fm) {
-            half8 b[NPL][4];
+            half8 b[NPL][RTW];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            for (int r = 0; r < RTW; ++r) {
                 const half8 t1 = decode8((fm >> 1) ? pw[r][0].y : pw[r][0].x, fm & 1) * al[r][0];
                 const half8 t2 = decode8((fm >> 1) ? pw[r][1].y : pw[r][1].x, fm & 1) * al[r][1];
                 if constexpr (FUSE) { b[0][r] = t1 + t2; } else { b[0][r] = t1; b[NPL - 1][r] = t2; }
             }
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) {
+            for (int mt = 0; mt < MTW; ++mt) {
                 const half8 a = __builtin_bit_cast(
                     half8, *reinterpret_cast<const uintx4 *>(xb + (mt >> 2) * (16 * kTileChunk) + (mt & 3) * 256 + fm * 64));
 #pragma unroll
                 for (int pl = 0; pl < NPL; ++pl)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
+                    for (int r = 0; r < RTW; ++r)
                         acc[r][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b[pl][r], acc[r][mt], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);       // keep the next field's expansion out of this one's registers
         }
     };
 
-    uintx2 pa[4][2], pb[4][2], sa[4], sb[4];
+    uintx2 pa[RTW][2], pb[RTW][2], sa[RTW], sb[RTW];
     stage(0, 0);
     load_group(pa, sa, 0);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) { pb[r][0] = pa[r][0]; pb[r][1] = pa[r][1]; sb[r] = sa[r]; }
+    for (int r = 0; r < RTW; ++r) { pb[r][0] = pa[r][0]; pb[r][1] = pa[r][1]; sb[r] = sa[r]; }
     __builtin_amdgcn_s_waitcnt(0);                   // this wave's chunks have landed in LDS
     __syncthreads();
 
@@ -863,7 +863,7 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
         }
     }
 
-    tile_store<4, 8>(acc, y, y_f16, rt_base, nl, M, N, ep, [&](int mt, int j) { return m0 + wm * 128 + mt * 16 + 4 * q + j; });
+    tile_store<RTW, MTW>(acc, y, y_f16, rt_base, nl, M, N, ep, [&](int mt, int j) { return m0 + mt * 16 + 4 * q + j; });
 }
 
 template <bool FUSE>
@@ -923,7 +923,7 @@ struct TileKind {
 };
 constexpr int kTileKindCount = 5;
 constexpr TileKind kTileKinds[kTileKindCount] = {
-    {16, 256, 256, {167.f, 121.f}, {0.73f, 0.50f}},   // gemm_tile3_kernel
+    {16, 256, 256, {167.f, 121.f}, {0.70f, 0.47f}},   // gemm_tile3_kernel
     {16, 128, 128, {97.f, 66.f}, {0.77f, 0.53f}},     // gemm_tile_kernel<8, ., 4>
     {8, 128, 64, {55.f, 44.f}, {0.75f, 0.54f}},       // gemm_tile_kernel<8, ., 2>
     {8, 64, 32, {32.f, 28.f}, {0.83f, 0.65f}},        // gemm_tile_kernel<4, ., 2>
