@@ -731,6 +731,19 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     tile_store<RTW, MTW>(acc, y, y_f16, rt_base, nl, M, N, ep, [&](int mt, int j) { return m0 + mt * 16 + 4 * q + j; });
 }
 
+// One direct global -> LDS load of 16 bytes per lane (lane l lands at lds_base + 16*l), written as inline assembly.
+// Through the compiler's builtin the same instruction makes the wait-count pass treat every later LDS wait of the wave
+// as "counters may retire out of order" until both counters have been drained: each s_waitcnt for an operand read
+// becomes lgkmcnt(0) and operand reads issued ahead of their use buy nothing.  Hidden from that pass, the loads are
+// waited for by hand (s_waitcnt vmcnt(0) before the barrier that publishes the buffer); loads the pass does not know
+// of can only make its own vmcnt waits stricter, never weaker, because the counter retires in issue order.
+__device__ __forceinline__ void lds_direct_load16(const void *gptr, const char *lds_base)
+{
+    const uint32_t lds_off = static_cast<uint32_t>(reinterpret_cast<size_t>(
+        (const __attribute__((address_space(3))) char *)lds_base));
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory", "m0");
+}
+
 // Large prefill tile: 256 rows x 256 tokens, eight waves along the rows (two per SIMD), each 2 row tiles x all 16
 // token tiles: every trit of the workgroup is expanded exactly once and used for 16 MFMAs (a 4 x 2 arrangement of
 // waves with 4 row tiles x 8 token tiles each expands every trit twice and measured 3-9 % slower, although it reads
@@ -774,10 +787,8 @@ gemm_tile3_kernel(const uint8_t *__restrict__ records, const uint16_t *__restric
             int m = tok0 + j;
             m = m < M ? m : M - 1;                   // rows past M: duplicates, never stored
             asm volatile("" : "+v"(m));              // recompute the row address here: eight hoisted 64-bit addresses would not fit
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(xcol + static_cast<size_t>(m) * K + g * 128),
-                (__attribute__((address_space(3))) void *)(xt + buf * kTile3BufBytes + ((w >> 1) * 16 + (w & 1) * 8 + j) * kTileChunk),
-                16, 0, 0);
+            lds_direct_load16(xcol + static_cast<size_t>(m) * K + g * 128,
+                              xt + buf * kTile3BufBytes + ((w >> 1) * 16 + (w & 1) * 8 + j) * kTileChunk);
         }
     };
 
