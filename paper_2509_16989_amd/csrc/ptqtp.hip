@@ -520,6 +520,19 @@ gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict
 // share its L2 copy of the packed rows.
 constexpr int kTileChunk = 1040;                    // 1 KiB chunk of four tokens + 16-byte skew (tiles with direct-to-LDS loads)
 
+// One direct global -> LDS load of 16 bytes per lane (lane l lands at lds_base + 16*l), written as inline assembly.
+// Through the compiler's builtin the same instruction makes the wait-count pass treat every later LDS wait of the wave
+// as "counters may retire out of order" until both counters have been drained: each s_waitcnt for an operand read
+// becomes lgkmcnt(0) and operand reads issued ahead of their use buy nothing.  Hidden from that pass, the loads are
+// waited for by hand (s_waitcnt vmcnt(0) before the barrier that publishes the buffer); loads the pass does not know
+// of can only make its own vmcnt waits stricter, never weaker, because the counter retires in issue order.
+__device__ __forceinline__ void lds_direct_load16(const void *gptr, const char *lds_base)
+{
+    const uint32_t lds_off = static_cast<uint32_t>(reinterpret_cast<size_t>(
+        (const __attribute__((address_space(3))) char *)lds_base));
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory", "m0");
+}
+
 // Epilogues of the MFMA tiles (the decode chain at many tokens): `gated` = the layer stacks N/2 gate rows over N/2
 // up rows and a wave's row tiles alternate gate, up of the same 16 outputs: out = silu(gate) * up; then, if
 // residual != null, out += residual[m][n] (fp16, same shape as the output).
@@ -619,9 +632,7 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
             int m = m0 + (c >> 4) * 64 + (c & 15) + (lane >> 4) * 16;
             m = m < M ? m : M - 1;                   // rows past M: duplicates, never stored
             asm volatile("" : "+v"(m));              // recompute the row address here instead of keeping TM/16 of them
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(xcol + static_cast<size_t>(m) * K + g * 128),
-                (__attribute__((address_space(3))) void *)(xt + buf * kBuf + c * kTileChunk), 16, 0, 0);
+            lds_direct_load16(xcol + static_cast<size_t>(m) * K + g * 128, xt + buf * kBuf + c * kTileChunk);
         }
     };
     // operand of token tile mt: tokens (mt%4)*16 + nl of block mt/4 -> chunk nl, run mt%4
@@ -729,19 +740,6 @@ gemm_tile_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict
     }
 
     tile_store<RTW, MTW>(acc, y, y_f16, rt_base, nl, M, N, ep, [&](int mt, int j) { return m0 + mt * 16 + 4 * q + j; });
-}
-
-// One direct global -> LDS load of 16 bytes per lane (lane l lands at lds_base + 16*l), written as inline assembly.
-// Through the compiler's builtin the same instruction makes the wait-count pass treat every later LDS wait of the wave
-// as "counters may retire out of order" until both counters have been drained: each s_waitcnt for an operand read
-// becomes lgkmcnt(0) and operand reads issued ahead of their use buy nothing.  Hidden from that pass, the loads are
-// waited for by hand (s_waitcnt vmcnt(0) before the barrier that publishes the buffer); loads the pass does not know
-// of can only make its own vmcnt waits stricter, never weaker, because the counter retires in issue order.
-__device__ __forceinline__ void lds_direct_load16(const void *gptr, const char *lds_base)
-{
-    const uint32_t lds_off = static_cast<uint32_t>(reinterpret_cast<size_t>(
-        (const __attribute__((address_space(3))) char *)lds_base));
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory", "m0");
 }
 
 // Large prefill tile: 256 rows x 256 tokens, eight waves along the rows (two per SIMD), each 2 row tiles x all 16
@@ -1231,9 +1229,7 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
                 int m = (c >> 4) * 32 + (c & 15) + (lane >> 5) * 16;
                 m = m < M ? m : M - 1;               // rows past M: duplicates, never stored
                 asm volatile("" : "+v"(m));          // keep the row address out of loop-invariant registers
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(x + static_cast<size_t>(m) * K + kc),
-                    (__attribute__((address_space(3))) void *)(xtile + buf * kBuf + c * kRowsChunk<MT>), 16, 0, 0);
+                lds_direct_load16(x + static_cast<size_t>(m) * K + kc, xtile + buf * kBuf + c * kRowsChunk<MT>);
             }
         }
     };
