@@ -947,7 +947,7 @@ struct TileKind {
 };
 constexpr int kTileKindCount = 5;
 constexpr TileKind kTileKinds[kTileKindCount] = {
-    {16, 256, 256, {167.f, 121.f}, {0.68f, 0.46f}},   // gemm_tile3_kernel
+    {16, 256, 256, {152.f, 104.f}, {0.68f, 0.46f}},   // gemm_tile3_kernel
     {16, 128, 128, {97.f, 66.f}, {0.77f, 0.53f}},     // gemm_tile_kernel<8, ., 4>
     {8, 128, 64, {55.f, 44.f}, {0.75f, 0.54f}},       // gemm_tile_kernel<8, ., 2>
     {8, 64, 32, {32.f, 28.f}, {0.83f, 0.65f}},        // gemm_tile_kernel<4, ., 2>
