@@ -1322,11 +1322,16 @@ hipError_t tile_stage(const uint8_t *records, const uint16_t *x, void *y, const 
     s.N = N; s.K = K; s.NG = K / 128;
     s.RT = (N + kTileRows - 1) / kTileRows;
     s.KS = (K + kStepK - 1) / kStepK;
+    const int kinds = gated ? kTileKindCount - 1 : kTileKindCount;
     int best = 1;
     double cost = 1e30;
-    for (int k = 0; k < (gated ? kTileKindCount - 1 : kTileKindCount); ++k) {
+    for (int k = 0; k < kinds; ++k) {
         const double c = tile_cost(k, fuse_planes ? 1 : 0, static_cast<int>(s.RT), M);
         if (c < cost) { cost = c; best = k; }
+    }
+    if (g_tune_tile_variant != 0) {                  // ptqtp_tune("tile_variant"), where the stage allows that tile
+        static const int kind_of_variant[6] = {0, 1, 2, 0, 3, 4};
+        if (kind_of_variant[g_tune_tile_variant] < kinds) best = kind_of_variant[g_tune_tile_variant];
     }
     return launch_tile_kind(best, fuse_planes, records, x, y, M, s, y_f16, stream, 0, -1, TileEpilogue{residual, gated});
 }

@@ -257,6 +257,28 @@ def test_chain_batch_fused_planes_stage(ptq, N, K, M, epi):
     assert np.all(np.abs(got - ref) <= 1e-5 * E + 2.0 ** -23 * np.abs(ref))
 
 
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("epi", ["none", "swiglu"])
+def test_chain_batch_every_tile_with_epilogue(ptq, variant, epi):
+    # each tile kind with the epilogue in its store, ragged rows and tokens (a gated stage cannot use the 64 x 64 tile,
+    # whose waves own one row tile: the override is ignored there)
+    N, K, M = 1184, 640, 290
+    lin = workloads.make_linear(N, K, 90, N)
+    x = workloads.make_x(M, K, 90, N)
+    n_out = N // 2 if epi == "swiglu" else N
+    r = workloads.make_x(M, n_out, 90, 7)
+    y = torch.full((M, n_out), float("nan"), dtype=torch.float16, device="cuda:0")
+    plan = ptq.ptqtp_chain_plan([dict(packed=pack(ptq, lin), x=dev(x), y=y, N=N, K=K, level=0, residual=dev(r),
+                                      epilogue=ptq.PTQTP_EPI_SWIGLU if epi == "swiglu" else ptq.PTQTP_EPI_NONE)])
+    try:
+        ptq.ptqtp_tune("tile_variant", variant)
+        ptq.ptqtp_chain_run_batch(plan, M)
+        torch.cuda.synchronize()
+    finally:
+        ptq.ptqtp_tune("tile_variant", 0)
+    check_stage(y, lin, x, epi, r)
+
+
 def test_chain_batch_in_place_residual_on_tiles(ptq):
     # y may be the stage's own residual buffer (the residual stream updated in place)
     N, K, M = 512, 384, 200
