@@ -1047,8 +1047,9 @@ template <int MT, int R, int S>
 hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
                              hipStream_t stream, const uint16_t *residual = nullptr, int gated = 0)
 {
-    // measured on 8B shapes: 8 waves per item, except for the register-heavy 64-token x 2-tile case
-    int W = g_tune_small_waves > 0 ? g_tune_small_waves : (MT * R >= 8 ? 2 : 8);
+    // measured: 8 waves per item, except for the register-heavy 64-token x 2-tile case: 2 waves there on 8B shapes
+    // (K = 4096), 4 on longer rows (70B down, K = 28672, at 64 tokens: 166 -> 105 us)
+    int W = g_tune_small_waves > 0 ? g_tune_small_waves : (MT * R >= 8 ? (s.KS > 16 ? 4 : 2) : 8);
     if (W > (MT * R >= 8 ? 4 : 8)) W = MT * R >= 8 ? 4 : 8;
     while (W > 1 && W > s.KS) W /= 2;
     const int64_t grid = gated ? s.RT / 2 : (s.RT + R - 1) / R;
