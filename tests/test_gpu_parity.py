@@ -560,6 +560,32 @@ def test_gemm_tile_fp16_output_and_guard(ptq, variant):
     assert (buf[:256] == 7).all() and (buf[256 + M * N:] == 7).all()
 
 
+@pytest.mark.parametrize("seed", range(32))
+def test_gemm_random_shapes(ptq, seed):
+    # seeded random shapes across all regimes of ptqtp_gemm (batch 1, small batch, chunks, every tile, ragged rows,
+    # tokens and an odd number of groups), fp32 / fp16 output, with and without the fused-plane flag
+    r = np.random.default_rng(1000 + seed)
+    N = int(r.integers(1, 1200))
+    K = 128 * int(r.integers(1, 21))
+    M = int(r.choice([1, int(r.integers(2, 17)), int(r.integers(17, 65)), int(r.integers(65, 256)), int(r.integers(256, 600))]))
+    f16 = bool(r.integers(0, 2))
+    fused = bool(r.integers(0, 2))
+    lin = workloads.make_linear(N, K, 91, seed)
+    x = workloads.make_x(M, K, 91, seed)
+    flags = (ptq.PTQTP_F16 if f16 else ptq.PTQTP_F32) | (ptq.PTQTP_FUSED_PLANES if fused else 0)
+    buf = torch.full((M * N + 256,), 7.0, dtype=torch.float16 if f16 else torch.float32, device="cuda:0")
+    out = buf[128:128 + M * N].view(M, N)
+    ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=flags, out=out)
+    assert (buf[:128] == 7).all() and (buf[128 + M * N:] == 7).all()
+    got = out.cpu().numpy().astype(np.float64)
+    ref, B = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+    rounding = 2.0 ** -10 * B if f16 else 0.0
+    assert np.all(np.abs(got - ref) <= TOL * B + rounding), (N, K, M, f16, fused)
+    if fused and M >= 256:
+        ref, B = oracle.forward_fused(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
+    assert np.all(np.abs(got - ref) <= 3e-5 * B + rounding), (N, K, M, f16, fused, float((np.abs(got - ref) / np.maximum(B, 1e-300)).max()))
+
+
 def test_gemm_small_rows_match_gemv(ptq):
     # each token of a batch gets the bits batch-1 would give it? not required (different
     # reduction trees are both correct) -- but both must sit inside the tight gate
