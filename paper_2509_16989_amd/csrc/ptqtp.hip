@@ -526,12 +526,19 @@ constexpr int kTileChunk = 1040;                    // 1 KiB chunk of four token
 // becomes lgkmcnt(0) and operand reads issued ahead of their use buy nothing.  Hidden from that pass, the loads are
 // waited for by hand (s_waitcnt vmcnt(0) before the barrier that publishes the buffer); loads the pass does not know
 // of can only make its own vmcnt waits stricter, never weaker, because the counter retires in issue order.
+// M0 (the LDS base of the load) is a register the compiler reserves for the few instructions that read it implicitly and
+// sets right before each of them; the kernels here contain none of those (no builtin LDS-direct loads, no indexed
+// register access, no messages), so writing it in the asm statement disturbs nothing -- the diagnostic about a reserved
+// register in the clobber list is silenced on that ground.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lds_direct_load16(const void *gptr, const char *lds_base)
 {
     const uint32_t lds_off = static_cast<uint32_t>(reinterpret_cast<size_t>(
         (const __attribute__((address_space(3))) char *)lds_base));
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // Epilogues of the MFMA tiles (the decode chain at many tokens): `gated` = the layer stacks N/2 gate rows over N/2
 // up rows and a wave's row tiles alternate gate, up of the same 16 outputs: out = silu(gate) * up; then, if
