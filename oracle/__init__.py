@@ -45,10 +45,9 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-def _load():
-    global _lib
-    if _lib is None:
-        lib = ctypes.CDLL(build())
+def _bind(lib):
+    """Declare the C signatures on a loaded library (the built one, or a deliberately broken copy in the mutation tests)."""
+    if True:
         p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         lib.ptqtp_oracle_half_to_double.restype = ctypes.c_double
         lib.ptqtp_oracle_half_to_double.argtypes = [ctypes.c_uint16]
@@ -76,7 +75,13 @@ def _load():
         lib.ptqtp_oracle_round_half.argtypes = [ctypes.c_double]
         lib.ptqtp_oracle_round_half_array.restype = None
         lib.ptqtp_oracle_round_half_array.argtypes = [p, i64, p]
-        _lib = lib
+    return lib
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = _bind(ctypes.CDLL(build()))
     return _lib
 
 

@@ -36,8 +36,13 @@
  * error never increasing in the trit step (the monotonicity the paper states); exactly ternary rows
  * recovered; exact invariance under power-of-two scaling; equivariance under permutations inside a
  * group; independence of units with a global stopping rule; the binary16 rounding against numpy's
- * on every finite value and every exact tie.  What the paper leaves open (the order of the lambda
- * update, the order of ties, which of the two stopping rules) is a reading, not a pin.
+ * on every finite value and every exact tie; the stopping rule on a run whose changes straddle eps
+ * between the norm and its square.  A further test plants one mistake at a time in a copy of this
+ * file (a dropped term, a wrong sign or index, a changed constant) and requires a pin to fail.
+ * What the paper leaves open (the order of the lambda update, the order of ties, which of the two
+ * stopping rules) is a reading, not a pin.  The cap lambda_max = 1 is carried from the paper but
+ * cannot be reached from the prescribed start at G = 128 (one raise multiplies lambda by
+ * sqrt(kappa / 1e6), and kappa is about 2G / lambda): no input exercises it.
  */
 #include <math.h>
 #include <stddef.h>

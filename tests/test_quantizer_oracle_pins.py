@@ -180,6 +180,24 @@ def test_units_are_independent_and_convergence_is_global():
     assert b >= max(a, c)
 
 
+def test_stopping_rule_is_the_norm_not_its_square():
+    # alpha after t iterations, for every t, from restarts with max_iters = t (the iteration is deterministic): the
+    # stopping iteration for a given eps then follows from the Frobenius norms of the changes alone
+    W = _w(4, 256, 12)
+    alphas = []
+    for t in range(0, 13):
+        q = oracle.quantize(W, max_iters=t, eps=0.0)
+        alphas.append(np.concatenate([q["a1_f64"].ravel(), q["a2_f64"].ravel()]))
+    deltas = np.array([np.sqrt(np.sum((alphas[t] - alphas[t - 1]) ** 2)) for t in range(1, 13)])   # change made by iteration t
+    t_star = 5
+    assert deltas[t_star - 1] < deltas[t_star - 2] < 1.0            # still shrinking there, and below 1 (so d*d < d)
+    eps = float(np.sqrt(deltas[t_star - 1] * deltas[t_star - 2]))  # between the changes of iterations t*-1 and t*
+    by_norm = 1 + int(np.argmax(deltas < eps))
+    by_square = 1 + int(np.argmax(deltas ** 2 < eps))
+    assert by_norm == t_star and by_square < by_norm                # the two rules really differ on this input
+    assert oracle.quantize(W, max_iters=50, eps=eps)["iters"] == by_norm
+
+
 def test_double_to_half_rounding_matches_numpy():
     r = np.random.default_rng(11)
     h = np.arange(0, 0x7c00, dtype=np.uint16).view(np.float16).astype(np.float64)      # every finite binary16 value
