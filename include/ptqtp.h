@@ -46,7 +46,9 @@ typedef int32_t ptqtp_status;
 enum {
     PTQTP_OK         = 0,
     PTQTP_ERR_NULL   = 1,  /* a required pointer is NULL                                   */
-    PTQTP_ERR_SHAPE  = 2,  /* M, N or K not positive, K % group != 0, M out of range       */
+    PTQTP_ERR_SHAPE  = 2,  /* M, N or K not positive, K % group != 0, M out of range, N or K
+                              above 2^30, or ceil(N/16) * ceil(K/256) above 2^27 (a packed
+                              layer of 292 GB)                                             */
     PTQTP_ERR_GROUP  = 3,  /* group size not supported (only 128)                          */
     PTQTP_ERR_SIZE   = 4,  /* packed_bytes / workspace_bytes smaller than required         */
     PTQTP_ERR_DTYPE  = 5,  /* y_dtype is neither PTQTP_F32 nor PTQTP_F16                   */
@@ -258,6 +260,8 @@ ptqtp_status ptqtp_chain_run_batch(const ptqtp_stage *stages, int32_t count, int
  *   workspace   device, >= ptqtp_quantize_workspace_bytes(N, K, group) bytes, 256-byte aligned
  * Stream-ordered, never synchronises: 2 launches per iteration; once the stopping rule has fired
  * the remaining launches return immediately.
+ * Errors: PTQTP_ERR_SHAPE for N or K above 2^30, N * K above 2^37, K % group != 0, max_iters outside
+ * 0..10000 or eps negative or NaN (the workspace size is 0 for such a shape); the others as above.
  */
 size_t ptqtp_quantize_workspace_bytes(int64_t N, int64_t K, int32_t group);
 ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t group, int32_t max_iters, double eps,

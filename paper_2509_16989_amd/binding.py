@@ -155,6 +155,7 @@ def ptqtp_pack(T1, T2, a1, a2, M: int = 1, group: int = 128, check: bool = True)
 
 
 def ptqtp_unpack(packed: torch.Tensor, N: int, K: int, M: int = 1, group: int = 128):
+    _check_blob(packed, N, K, group, "ptqtp_unpack")
     dev = packed.device
     T1 = torch.empty((N, K), dtype=torch.int8, device=dev)
     T2 = torch.empty((N, K), dtype=torch.int8, device=dev)
@@ -167,10 +168,22 @@ def ptqtp_unpack(packed: torch.Tensor, N: int, K: int, M: int = 1, group: int = 
     return T1, T2, a1, a2
 
 
+def _check_blob(packed: torch.Tensor, N: int, K: int, group: int, where: str) -> None:
+    """The kernels trust N and K: a blob shorter than those need would be read past its end."""
+    need = ptqtp_packed_bytes(1, N, K, group)
+    if need == 0:
+        raise PtqtpError(2 if group == 128 else 3, where)
+    if packed.numel() < need:
+        raise PtqtpError(4, where)
+
+
 def _forward(fn, where, packed, x, N, K, M, group, y_dtype, out):
     ydt = torch.float32 if (y_dtype & ~PTQTP_FUSED_PLANES) == PTQTP_F32 else torch.float16
+    _check_blob(packed, N, K, group, where)
     if out is None:
         out = torch.empty((M, N), dtype=ydt, device=x.device)
+    elif out.numel() != M * N:
+        raise PtqtpError(2, where)
     st = fn(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"), _dev(out, ydt, "y"), y_dtype,
             M, N, K, group, None, 0, _stream())
     if st:
@@ -208,8 +221,8 @@ class _Linear(ctypes.Structure):
 class BatchPlan:
     """Device-side table for ptqtp_gemv_batch; keeps the tensors it names alive."""
 
-    def __init__(self, plan: torch.Tensor, items: int, keep):
-        self.plan, self.items, self._keep = plan, items, keep
+    def __init__(self, plan: torch.Tensor, items: int, keep, tokens: int):
+        self.plan, self.items, self._keep, self.tokens = plan, items, keep, tokens
 
 
 def ptqtp_gemv_batch_plan(linears, group: int = 128, y_dtype: int = PTQTP_F32) -> BatchPlan:
@@ -217,9 +230,12 @@ def ptqtp_gemv_batch_plan(linears, group: int = 128, y_dtype: int = PTQTP_F32) -
     ydt = torch.float32 if y_dtype == PTQTP_F32 else torch.float16
     n = len(linears)
     arr = (_Linear * max(n, 1))()
+    tokens = None
     for i, (packed, x, y, N, K) in enumerate(linears):
-        if x.numel() % K or y.numel() % N or x.numel() // K != y.numel() // N:
+        if N <= 0 or K <= 0 or x.numel() == 0 or x.numel() % K or y.numel() % N or x.numel() // K != y.numel() // N:
             raise PtqtpError(2, "ptqtp_gemv_batch_plan")
+        _check_blob(packed, N, K, group, "ptqtp_gemv_batch_plan")
+        tokens = x.numel() // K if tokens is None else min(tokens, x.numel() // K)
         arr[i] = _Linear(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"), _dev(y, ydt, "y"), N, K)
     lib = _load()
     nbytes = int(lib.ptqtp_batch_plan_bytes(arr, n, group))
@@ -230,11 +246,13 @@ def ptqtp_gemv_batch_plan(linears, group: int = 128, y_dtype: int = PTQTP_F32) -
     st = lib.ptqtp_gemv_batch_plan(arr, n, y_dtype, group, plan.data_ptr(), nbytes, _stream())
     if st:
         raise PtqtpError(st, "ptqtp_gemv_batch_plan")
-    return BatchPlan(plan, items, [t for lin in linears for t in lin[:3]])
+    return BatchPlan(plan, items, [t for lin in linears for t in lin[:3]], tokens)
 
 
 def ptqtp_gemm_batch(plan: BatchPlan, M: int) -> None:
     """Run a plan whose x tensors are [M, K] and y tensors [M, N]."""
+    if M > plan.tokens:
+        raise PtqtpError(2, "ptqtp_gemm_batch")
     st = _load().ptqtp_gemm_batch(plan.plan.data_ptr(), plan.items, int(M), _stream())
     if st:
         raise PtqtpError(st, "ptqtp_gemm_batch")
@@ -279,8 +297,8 @@ class _Stage(ctypes.Structure):
 class ChainPlan:
     """Device-side table for ptqtp_chain_run; keeps the host stage array and the tensors it names alive."""
 
-    def __init__(self, plan: torch.Tensor, arr, count: int, group: int, keep):
-        self.plan, self.arr, self.count, self.group, self._keep = plan, arr, count, group, keep
+    def __init__(self, plan: torch.Tensor, arr, count: int, group: int, keep, tokens: int):
+        self.plan, self.arr, self.count, self.group, self._keep, self.tokens = plan, arr, count, group, keep, tokens
 
 
 def ptqtp_chain_plan(stages, group: int = 128) -> ChainPlan:
@@ -290,11 +308,22 @@ def ptqtp_chain_plan(stages, group: int = 128) -> ChainPlan:
     n = len(stages)
     arr = (_Stage * max(n, 1))()
     keep = []
+    tokens = None
     for i, s in enumerate(stages):
         y = s["y"]
         if y.dtype not in (torch.float32, torch.float16):
             raise PtqtpError(5, "ptqtp_chain_plan")
         res = s.get("residual")
+        # the buffers must hold what the stage reads and writes: m tokens of K inputs, m x n_out outputs
+        N, K = int(s["N"]), int(s["K"])
+        n_out = N // 2 if int(s.get("epilogue", PTQTP_EPI_NONE)) == PTQTP_EPI_SWIGLU else N
+        if N <= 0 or K <= 0 or n_out <= 0:
+            raise PtqtpError(2, "ptqtp_chain_plan")
+        m = min(s["x"].numel() // K, y.numel() // n_out, *([res.numel() // n_out] if res is not None else []))
+        if m < 1:
+            raise PtqtpError(2, "ptqtp_chain_plan")
+        _check_blob(s["packed"], N, K, group, "ptqtp_chain_plan")
+        tokens = m if tokens is None else min(tokens, m)
         arr[i] = _Stage(_dev(s["packed"], torch.uint8, "packed"), _dev(s["x"], torch.float16, "x"), _dev(y, y.dtype, "y"),
                         _dev(res, torch.float16, "residual") if res is not None else None,
                         int(s["N"]), int(s["K"]), int(s.get("epilogue", PTQTP_EPI_NONE)),
@@ -309,18 +338,21 @@ def ptqtp_chain_plan(stages, group: int = 128) -> ChainPlan:
     st = lib.ptqtp_chain_plan(arr, n, group, plan.data_ptr(), nbytes, _stream())
     if st:
         raise PtqtpError(st, "ptqtp_chain_plan")
-    return ChainPlan(plan, arr, n, group, keep)
+    return ChainPlan(plan, arr, n, group, keep, tokens)
 
 
 def ptqtp_chain_run(plan: ChainPlan) -> None:
-    """One launch per level on the current stream."""
+    """One token: one launch per level on the current stream."""
     st = _load().ptqtp_chain_run(plan.arr, plan.count, plan.group, plan.plan.data_ptr(), _stream())
     if st:
         raise PtqtpError(st, "ptqtp_chain_run")
 
 
 def ptqtp_chain_run_batch(plan: ChainPlan, M: int) -> None:
-    """The chain at M tokens per stage (x [M,K], y / residual [M,n_out]); one launch per stage."""
+    """The chain at M tokens per stage (x [M,K], y / residual [M,n_out]); one launch per stage.  M may not exceed
+    what the smallest buffer named in the plan holds."""
+    if M > plan.tokens:
+        raise PtqtpError(2, "ptqtp_chain_run_batch")
     st = _load().ptqtp_chain_run_batch(plan.arr, plan.count, plan.group, int(M), _stream())
     if st:
         raise PtqtpError(st, "ptqtp_chain_run_batch")

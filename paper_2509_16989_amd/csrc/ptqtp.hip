@@ -61,9 +61,14 @@ inline bool make_shape(int64_t M, int64_t N, int64_t K, int32_t group, Shape *s,
     s->N = N; s->K = K; s->NG = K / group;
     s->RT = (N + kTileRows - 1) / kTileRows;
     s->KS = (K + kStepK - 1) / kStepK;
+    // at most 2^27 records (a blob of 292 GB, more than the device holds): record counts and the
+    // grids derived from them then fit 32 bits
+    if (s->RT * s->KS > (1ll << 27)) { *st = PTQTP_ERR_SHAPE; return false; }
     *st = PTQTP_OK;
     return true;
 }
+
+constexpr int64_t kMaxGrid = 0x7fffffff;      // workgroups of one launch (x dimension)
 
 inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -905,6 +910,7 @@ hipError_t launch_gemm_tile3(const uint8_t *records, const uint16_t *x, void *y,
     const int64_t units = ep.gated ? s.RT / 2 : s.RT, per = ep.gated ? 8 : 16;   // pairs per workgroup when gated
     const int NB = nb1 >= 0 ? nb1 : static_cast<int>((units + per - 1) / per);
     const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
+    if (grid <= 0 || grid > kMaxGrid) return hipErrorInvalidValue;
     const size_t lds = 2 * static_cast<size_t>(kTile3BufBytes);
     static bool configured = false;                  // raise the dynamic LDS limit once per process
     if (!configured) {
@@ -930,6 +936,7 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     const int64_t units = ep.gated ? s.RT / 2 : s.RT, per = ep.gated ? NRT / 2 : NRT;
     const int NB = nb1 >= 0 ? nb1 : static_cast<int>((units + per - 1) / per);
     const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
+    if (grid <= 0 || grid > kMaxGrid) return hipErrorInvalidValue;
     const size_t lds = 2 * static_cast<size_t>(TM / 4) * kTileChunk;
     static bool configured = false;                  // raise the dynamic LDS limit once per process
     if (!configured) {
@@ -1011,6 +1018,9 @@ hipError_t launch_tile_kind(int k, bool fuse, const uint8_t *records, const uint
     }
 #undef PTQTP_TILE
 }
+
+// ptqtp_tune("tile_variant", v): the tile kind that value v forces (0 = the cost model chooses)
+constexpr int kVariantKind[6] = {0, 1, 2, 0, 3, 4};
 
 int g_tune_small_waves = 0, g_tune_tile = 0, g_tune_small_rows = 0, g_tune_small_rows_kernel = -1, g_tune_tile_variant = 0, g_tune_small_fold = -1;
 
@@ -1338,8 +1348,7 @@ hipError_t tile_stage(const uint8_t *records, const uint16_t *x, void *y, const 
         if (c < cost) { cost = c; best = k; }
     }
     if (g_tune_tile_variant != 0) {                  // ptqtp_tune("tile_variant"), where the stage allows that tile
-        static const int kind_of_variant[6] = {0, 1, 2, 0, 3, 4};
-        if (kind_of_variant[g_tune_tile_variant] < kinds) best = kind_of_variant[g_tune_tile_variant];
+        if (kVariantKind[g_tune_tile_variant] < kinds) best = kVariantKind[g_tune_tile_variant];
     }
     return launch_tile_kind(best, fuse_planes, records, x, y, M, s, y_f16, stream, 0, -1, TileEpilogue{residual, gated});
 }
@@ -1379,8 +1388,7 @@ Route choose_route(const Shape &s, int M, bool fuse_planes)
     }
     r.path = PTQTP_ROUTE_TILE;
     if (g_tune_tile_variant != 0) {
-        static const int kind_of_variant[6] = {0, 1, 2, 0, 3, 4};
-        r.kind = kind_of_variant[g_tune_tile_variant];
+        r.kind = kVariantKind[g_tune_tile_variant];
         return r;
     }
     const int fz = fuse_planes ? 1 : 0;
@@ -1511,6 +1519,7 @@ ptqtp_status ptqtp_unpack(const void *packed, int64_t M, int64_t N, int64_t K, i
     const uint8_t *blob = static_cast<const uint8_t *>(packed);
     if (T1 || T2) {
         const int64_t blocks = (s.N * s.K + 255) / 256;
+        if (blocks > kMaxGrid) return PTQTP_ERR_SHAPE;
         hipLaunchKernelGGL(unpack_trits_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, blob, T1,
                            T2, s.N, s.K, s.KS);
     }

@@ -310,8 +310,14 @@ inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintp
 
 extern "C" {
 
+// N and K up to 2^30 each and N * K up to 2^37 (a binary16 matrix of 275 GB): unit and element counts,
+// and the grids derived from them, then fit 32 bits
+static bool quantize_shape_ok(int64_t N, int64_t K, int32_t group) {
+    return N > 0 && K > 0 && K % group == 0 && N <= (1ll << 30) && K <= (1ll << 30) && N * K <= (1ll << 37);
+}
+
 size_t ptqtp_quantize_workspace_bytes(int64_t N, int64_t K, int32_t group) {
-    if (group != kGroup || N <= 0 || K <= 0 || K % group != 0 || N > (1ll << 30) || K > (1ll << 30)) return 0;
+    if (group != kGroup || !quantize_shape_ok(N, K, group)) return 0;
     const size_t units = static_cast<size_t>(N) * static_cast<size_t>(K / group);
     return sizeof(QuantFlags) + units * 4 * sizeof(double);      // alpha (2), lambda, delta2
 }
@@ -322,8 +328,7 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
 {
     if (!W || !T1 || !T2 || !a1 || !a2 || !workspace) return PTQTP_ERR_NULL;
     if (group != kGroup) return PTQTP_ERR_GROUP;
-    if (N <= 0 || K <= 0 || K % group != 0 || N > (1ll << 30) || K > (1ll << 30) || max_iters < 0 || max_iters > 10000 ||
-        !(eps >= 0.0))
+    if (!quantize_shape_ok(N, K, group) || max_iters < 0 || max_iters > 10000 || !(eps >= 0.0))
         return PTQTP_ERR_SHAPE;
     const size_t need = ptqtp_quantize_workspace_bytes(N, K, group);
     if (workspace_bytes < need) return PTQTP_ERR_SIZE;

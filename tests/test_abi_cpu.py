@@ -137,11 +137,61 @@ def test_quantize_validation(lib):
     assert lib.ptqtp_quantize(*args(ws=None)) == 1
     assert lib.ptqtp_quantize(*args(group=64)) == 3
     assert lib.ptqtp_quantize(*args(K=200)) == 2
+    assert lib.ptqtp_quantize(*args(N=1 << 20, K=1 << 18)) == 2          # N * K above 2^37
+    assert lib.ptqtp_quantize_workspace_bytes(1 << 20, 1 << 18, 128) == 0
+    assert lib.ptqtp_quantize_workspace_bytes(1 << 20, 1 << 17, 128) == 256 + (1 << 30) * 32
     assert lib.ptqtp_quantize(*args(iters=-1)) == 2
     assert lib.ptqtp_quantize(*args(eps=-1.0)) == 2
     assert lib.ptqtp_quantize(*args(eps=float("nan"))) == 2
     assert lib.ptqtp_quantize(*args(wsb=100)) == 4
     assert lib.ptqtp_quantize(*args(ws=ctypes.c_void_p(0x10010))) == 6
+
+
+def test_size_limits(lib):
+    """N and K up to 2^30 each, and at most 2^27 records per layer: beyond that no grid or count fits 32 bits."""
+    assert lib.ptqtp_packed_bytes(1, 1 << 21, 1 << 17, 128) == 256 + (1 << 26) * 2176     # 2^17 x 2^9 records
+    assert lib.ptqtp_packed_bytes(1, 1 << 22, 1 << 17, 128) == 256 + (1 << 27) * 2176     # the limit itself
+    assert lib.ptqtp_packed_bytes(1, (1 << 22) + 1, 1 << 17, 128) == 0
+    assert lib.ptqtp_packed_bytes(1, 1 << 30, 1 << 30, 128) == 0
+    assert lib.ptqtp_packed_bytes(1, (1 << 30) + 16, 128, 128) == 0
+    route = (ctypes.c_int32 * 4)()
+    assert lib.ptqtp_gemm_route(512, 1 << 30, 1 << 30, 128, 0, route) == 2
+
+
+def test_binding_rejects_short_buffers_before_any_launch():
+    """The kernels trust N and K, so the binding compares them with the buffers it is handed (host tensors suffice
+    to show it: the size checks come before the device checks)."""
+    import torch
+    import paper_2509_16989_amd as ptq
+    N, K = 64, 256
+    need = ptq.ptqtp_packed_bytes(1, N, K)
+    short = torch.zeros(need - 1, dtype=torch.uint8)
+    x = torch.zeros(K, dtype=torch.float16)
+    with pytest.raises(ptq.PtqtpError) as e:
+        ptq.ptqtp_gemv(short, x, N, K)
+    assert e.value.status == 4
+    with pytest.raises(ptq.PtqtpError) as e:
+        ptq.ptqtp_gemm(short, x.reshape(1, K), N, K)
+    assert e.value.status == 4
+    with pytest.raises(ptq.PtqtpError) as e:
+        ptq.ptqtp_unpack(short, N, K)
+    assert e.value.status == 4
+    full = torch.zeros(need, dtype=torch.uint8)
+    with pytest.raises(ptq.PtqtpError) as e:                   # output of the wrong size
+        ptq.ptqtp_gemm(full, x.reshape(1, K), N, K, out=torch.zeros(N - 1))
+    assert e.value.status == 2
+    with pytest.raises(ptq.PtqtpError) as e:
+        ptq.ptqtp_gemv_batch_plan([(short, x, torch.zeros(N), N, K)])
+    assert e.value.status == 4
+    with pytest.raises(ptq.PtqtpError) as e:                   # y holds fewer tokens than x
+        ptq.ptqtp_gemv_batch_plan([(full, torch.zeros(2 * K, dtype=torch.float16), torch.zeros(N), N, K)])
+    assert e.value.status == 2
+    with pytest.raises(ptq.PtqtpError) as e:
+        ptq.ptqtp_chain_plan([dict(packed=short, x=x, y=torch.zeros(N), N=N, K=K)])
+    assert e.value.status == 4
+    with pytest.raises(ptq.PtqtpError) as e:                   # a gated stage writes N/2 outputs: room for none here
+        ptq.ptqtp_chain_plan([dict(packed=full, x=x, y=torch.zeros(N // 2 - 1), N=N, K=K, epilogue=ptq.PTQTP_EPI_SWIGLU)])
+    assert e.value.status == 2
 
 
 def test_status_strings_and_version(lib):
