@@ -72,6 +72,28 @@ MUTATIONS = [
      "if (rem > 0.5 || (rem == 0.5 && fmod(r, 2.0) == 1.0)) r += 1.0;", "if (rem > 1.5) r += 1.0;"),
     ("ptqtp_block_oracle.c", "test_block_oracle_pins", "silu with the sign of the exponent flipped",
      "return z / (1.0 + exp(-z));", "return z / (1.0 + exp(z));"),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "sigmoid alone instead of z * sigmoid",
+     "return z / (1.0 + exp(-z));", "return 1.0 / (1.0 + exp(-z));"),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "gate and up halves swapped",
+     "ptqtp_oracle_silu(y[m * 2 * I + i]) * y[m * 2 * I + I + i]",
+     "ptqtp_oracle_silu(y[m * 2 * I + I + i]) * y[m * 2 * I + i]"),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "gate and up interleaved instead of stacked",
+     "ptqtp_oracle_silu(y[m * 2 * I + i]) * y[m * 2 * I + I + i]",
+     "ptqtp_oracle_silu(y[m * 2 * I + 2 * i]) * y[m * 2 * I + 2 * i + 1]"),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "residual subtracted",
+     "out[i] = y[i] + half_bits_to_double(r[i]);", "out[i] = y[i] - half_bits_to_double(r[i]);"),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "residual widened with the exponent off by one",
+     "else              v = ldexp((double)(1024 + frac), e - 25);", "else              v = ldexp((double)(1024 + frac), e - 24);"),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "binary16 rounding with an 11-bit fraction",
+     "double quantum = ldexp(1.0, lead - 10);", "double quantum = ldexp(1.0, lead - 11);"),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "binary16 rounding: ties away from zero",
+     "double q = nearbyint(a / quantum) * quantum;", "double q = round(a / quantum) * quantum;"),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "binary16 rounding: no overflow to infinity",
+     "if (q >= 65520.0) q = INFINITY;", ""),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "binary16 rounding: no subnormal range",
+     "if (lead < -14) lead = -14;", ""),
+    ("ptqtp_block_oracle.c", "test_block_oracle_pins", "binary16 rounding: sign lost",
+     "return v < 0 ? -q : q;", "return q;"),
 ]
 
 
