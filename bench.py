@@ -443,9 +443,10 @@ def cpu_baseline(layer0, names):
     total_bytes = 0
     t_total = 0.0
     reps = 0
-    budget = 15.0
+    budget = 15.0                                   # wall-clock cap, seconds
     t_start = time.perf_counter()
-    while time.perf_counter() - t_start < budget and reps < 3:
+    # at least 3 passes and about 16 CPU-seconds of oracle work (wall time x threads), whichever comes later
+    while time.perf_counter() - t_start < budget and (reps < 3 or t_total * threads < 16.0):
         for name in names:
             lin = layer0[name]
             x = workloads.x_for(name, 1, lin["K"], 1, 0)
@@ -456,7 +457,8 @@ def cpu_baseline(layer0, names):
         reps += 1
     return {"value": round(total_bytes / t_total / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"layer 0 of the stack (seven 8B-shaped linears, batch 1), {reps} pass(es), "
-                      f"{t_total / reps * 1e3:.0f} ms per layer; same algorithmic bytes as the GPU figure",
+                      f"{t_total / reps * 1e3:.0f} ms per layer, {t_total * threads:.0f} CPU-seconds in all; "
+                      "same algorithmic bytes as the GPU figure",
             "us_per_decode_step_extrapolated": round(t_total / reps * 32 * 1e6)}
 
 
