@@ -77,80 +77,177 @@ inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintp
 // ------------------------------------------------------------------------------------------
 __global__ void clear_status_kernel(int32_t *st) { *st = 0; }
 
-// One workgroup per record; threads 0..511 build one 32-bit plane word each, 512..575 one scale.
-__global__ void __launch_bounds__(576)
+// Four trits held as int8 bytes of x -> their 2-bit codes at nibble j of a 16-bit result, the nonzero bit at nibble
+// bit 1 - par and the sign at 3 - par (the layout of one parity of a plane word).  For a valid byte (0x00, 0x01, 0xff)
+// bit 0 says nonzero and bit 7 says negative.  `bad` collects, as nonzero bits, every byte that is none of the three.
+__device__ __forceinline__ uint32_t code4(uint32_t x, int par, uint32_t &bad) {
+    const uint32_t nz = x & 0x01010101u, sg = (x >> 7) & 0x01010101u;
+    const uint32_t neg = (sg << 8) - sg;                   // 0xff in the bytes whose sign bit is set
+    bad |= x ^ (nz | neg);                                 // a valid byte is rebuilt exactly
+    uint32_t c = (nz << (1 - par)) | (sg << (3 - par));    // bits at 8j + {1 - par, 3 - par}
+    c = (c | (c >> 4)) & 0x00ff00ffu;                      // byte 1 -> nibble 1, byte 3 -> nibble 5
+    return (c | (c >> 8)) & 0xffffu;                       // nibbles 4, 5 -> 2, 3
+}
+
+// Eight 2-bit codes of one parity of a plane word (half = 0: nibbles 0..3, 1: nibbles 4..7) -> four int8 trits
+__device__ __forceinline__ uint32_t trits4(uint32_t w, int par, int half) {
+    uint32_t t = (w >> (16 * half + 1 - par)) & 0x5555u;   // per nibble: nonzero at bit 0, sign at bit 2
+    t = (t | (t << 8)) & 0x00ff00ffu;
+    t = (t | (t << 4)) & 0x0f0f0f0fu;                      // one nibble per byte
+    const uint32_t nz = t & 0x01010101u, sg = (t >> 2) & 0x01010101u;
+    const uint32_t neg = (sg << 8) - sg, any = (nz << 8) - nz;   // 0xff where negative / where nonzero
+    return (neg & any) | nz;                               // 0xff, 0x01 or 0x00 per byte
+}
+
+// One workgroup of 256 threads per kPackRecs consecutive records of a row tile (a row's bytes for them are
+// contiguous: up to 512 bytes).  Their 16 rows x 256 columns of both planes (8 KB of int8 per record) come in through
+// LDS with 16-byte loads, all of a thread's loads in flight at once; then every thread builds one 32-bit word per
+// plane and record from two 8-byte LDS reads, and threads 0..63 store one scale per record.
+// VEC: both planes are 16-byte aligned (K is a multiple of 128, so every row segment then is).
+constexpr int kPackRecs = 2;      // measured: 1 and 2 alike, 4 slower (LDS per workgroup limits the workgroups per CU)
+
+template <bool VEC>
+__global__ void __launch_bounds__(256)
 pack_kernel(const int8_t *__restrict__ T1, const int8_t *__restrict__ T2,
             const uint16_t *__restrict__ a1, const uint16_t *__restrict__ a2,
             uint8_t *__restrict__ blob, int64_t N, int64_t K, int64_t RT, int64_t KS, int64_t NG,
             int32_t *__restrict__ dev_status)
 {
-    const int64_t recno = blockIdx.x;
-    const int64_t rt = recno / KS, ks = recno % KS;
-    uint8_t *rec = blob + kHeaderBytes + recno * kRecordBytes;
+    // LDS holds the 8-byte trit groups in the order their readers come: slot par*256 + u is what thread u reads for
+    // parity par (consecutive threads, consecutive slots: no bank conflicts on the read side)
+    __shared__ uintx2 slots[kPackRecs][2][512];
+    const int64_t per_rt = (KS + kPackRecs - 1) / kPackRecs;
+    const int64_t rt = blockIdx.x / per_rt, ks0 = (blockIdx.x % per_rt) * kPackRecs;
     const int t = threadIdx.x;
-    if (recno == 0 && t == 0) {
+    if (blockIdx.x == 0 && t == 0) {
         BlobHeader h;
         h.magic = kMagic; h.layout = kLayoutId; h.group = 128; h.N = N; h.K = K; h.RT = RT; h.KS = KS;
         *reinterpret_cast<BlobHeader *>(blob) = h;
     }
-    if (recno == 0 && t >= 12 && t < 64) reinterpret_cast<uint32_t *>(blob)[t] = 0;  // header tail (48..255)
-    if (t < 512) {
-        const int plane = t >> 8, lane = (t >> 2) & 63, i = t & 3;
-        const int nl = lane & 15, q = lane >> 4;
-        const int64_t n = rt * kTileRows + nl;
-        const int8_t *T = plane ? T2 : T1;
-        uint32_t word = 0;
-        bool bad = false;
-        if (n < N) {
+    if (blockIdx.x == 0 && t >= 12 && t < 64) reinterpret_cast<uint32_t *>(blob)[t] = 0;  // header tail (48..255)
+
+    // thread -> row t/16, 16-byte segment t%16 of both planes of every record; rows past N and columns past K read as zero
+    const int row = t >> 4, seg = t & 15;
+    const int64_t n = rt * kTileRows + row;
+    uintx4 v[kPackRecs][2];
+    uint16_t scale[kPackRecs];
 #pragma unroll
-            for (int par = 0; par < 2; ++par) {
-                const int f = 2 * i + par;
-                const int64_t k = ks * kStepK + (f >> 2) * 128 + (f & 3) * 32 + q * 8;
-                if (k < K) {
+    for (int r = 0; r < kPackRecs; ++r) {
+        const int64_t k = (ks0 + r) * kStepK + seg * 16;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        int v = T[n * K + k + j];
-                        if (v < -1 || v > 1) { bad = true; v = 0; }
-                        const uint32_t code = static_cast<uint32_t>(v) & 3u;       // (sign, nonzero)
-                        word |= ((code >> 1) << (4 * j + 3 - par)) | ((code & 1u) << (4 * j + 1 - par));
-                    }
+        for (int plane = 0; plane < 2; ++plane) {
+            v[r][plane] = uintx4{0u, 0u, 0u, 0u};
+            if (n < N && k < K) {
+                const int8_t *src = (plane ? T2 : T1) + n * K + k;
+                if (VEC) v[r][plane] = load_global<uintx4>(src);
+                else {
+                    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) w[b >> 2] |= static_cast<uint32_t>(static_cast<uint8_t>(src[b])) << (8 * (b & 3));
+                    v[r][plane] = uintx4{w[0], w[1], w[2], w[3]};
                 }
             }
         }
-        reinterpret_cast<uint32_t *>(rec)[t] = word;
-        if (bad && dev_status) atomicOr(dev_status, 1);
-    } else {
-        const int e = t - 512;           // 0..63: row nl = e/4, slot j = e%4
-        const int nl = e >> 2, j = e & 3;
-        const int64_t n = rt * kTileRows + nl;
-        const int64_t g = ks * 2 + (j & 1);
-        uint16_t v = 0;
-        if (n < N && g < NG) v = (j >> 1) ? a2[n * NG + g] : a1[n * NG + g];
-        reinterpret_cast<uint16_t *>(rec + 2 * kPlaneBytes)[e] = v;
+        scale[r] = 0;
+        if (t < 64) {                    // row nl = t/4, slot j = t%4: {a1[g0], a1[g1], a2[g0], a2[g1]}
+            const int64_t ns = rt * kTileRows + (t >> 2), g = (ks0 + r) * 2 + (t & 1);
+            if (ns < N && g < NG) scale[r] = ((t >> 1) & 1) ? a2[ns * NG + g] : a1[ns * NG + g];
+        }
     }
+    {
+        // the 16 bytes are field f = seg/2 of quarter-lanes q0 and q0 + 1: word f/2, parity f%2 of lanes q*16 + row
+        const int f = seg >> 1, q0 = (seg & 1) * 2;
+        const int sa = (f & 1) * 256 + (q0 * 16 + row) * 4 + (f >> 1), sb = sa + 64;
+#pragma unroll
+        for (int r = 0; r < kPackRecs; ++r)
+#pragma unroll
+            for (int plane = 0; plane < 2; ++plane) {
+                slots[r][plane][sa] = uintx2{v[r][plane].x, v[r][plane].y};
+                slots[r][plane][sb] = uintx2{v[r][plane].z, v[r][plane].w};
+            }
+    }
+    __syncthreads();
+    uint32_t bad = 0;
+#pragma unroll
+    for (int r = 0; r < kPackRecs; ++r) {
+        if (ks0 + r >= KS) break;                                          // uniform
+        uint8_t *rec = blob + kHeaderBytes + (rt * KS + ks0 + r) * kRecordBytes;
+#pragma unroll
+        for (int plane = 0; plane < 2; ++plane) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int par = 0; par < 2; ++par) {
+                const uintx2 b8 = slots[r][plane][par * 256 + t];
+                uint32_t wrong = 0;
+                const uint32_t lo = code4(b8.x, par, wrong), hi = code4(b8.y, par, wrong);
+                // a byte outside {-1, 0, +1} is flagged and packed as 0: drop the codes of its nibble
+                if (wrong) {
+                    uint32_t keep = 0;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if ((((j < 4 ? b8.x : b8.y) >> (8 * (j & 3))) + 1u & 0xffu) < 3u) keep |= 0xfu << (4 * j);
+                    word |= (lo | (hi << 16)) & keep;
+                    bad = 1;
+                } else {
+                    word |= lo | (hi << 16);
+                }
+            }
+            reinterpret_cast<uint32_t *>(rec + plane * kPlaneBytes)[t] = word;
+        }
+        if (t < 64) reinterpret_cast<uint16_t *>(rec + 2 * kPlaneBytes)[t] = scale[r];
+    }
+    if (bad && dev_status) atomicOr(dev_status, 1);
 }
 
-// One thread per (n, k): pulls the trit of both planes back out of its record.
+// The mirror of pack_kernel: one workgroup of 256 threads per kPackRecs consecutive records of a row tile.  The
+// plane words come in through LDS (thread t: word t of each plane of each record, all loads in flight at once);
+// then thread t writes 16 consecutive columns of row t/16 per record and plane with one 16-byte store: those columns
+// are field f = (t%16)/2, quarter-lanes q and q+1, all eight nibbles of word f/2 at parity f%2.
+// VEC: the output planes are 16-byte aligned; otherwise bytes.
+template <bool VEC>
 __global__ void __launch_bounds__(256)
 unpack_trits_kernel(const uint8_t *__restrict__ blob, int8_t *__restrict__ T1, int8_t *__restrict__ T2,
                     int64_t N, int64_t K, int64_t KS)
 {
-    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (idx >= N * K) return;
-    const int64_t n = idx / K, k = idx % K;
-    const int64_t rt = n / kTileRows, ks = k / kStepK;
-    const int nl = static_cast<int>(n % kTileRows);
-    const int kk = static_cast<int>(k % kStepK);
-    const int g2 = kk >> 7, fm = (kk >> 5) & 3, q = (kk >> 3) & 3, j = kk & 7;
-    const int f = g2 * 4 + fm, lane = q * 16 + nl, i = f >> 1, par = f & 1;
-    const uint8_t *rec = blob + kHeaderBytes + (rt * KS + ks) * kRecordBytes;
+    __shared__ uint32_t words[kPackRecs][2][256];
+    const int64_t per_rt = (KS + kPackRecs - 1) / kPackRecs;
+    const int64_t rt = blockIdx.x / per_rt, ks0 = (blockIdx.x % per_rt) * kPackRecs;
+    const int t = threadIdx.x;
+    uint32_t w[kPackRecs][2];
 #pragma unroll
-    for (int plane = 0; plane < 2; ++plane) {
-        int8_t *T = plane ? T2 : T1;
-        if (!T) continue;
-        const uint32_t w = reinterpret_cast<const uint32_t *>(rec + plane * kPlaneBytes)[lane * 4 + i];
-        const uint32_t sign = (w >> (4 * j + 3 - par)) & 1u, nz = (w >> (4 * j + 1 - par)) & 1u;
-        T[idx] = static_cast<int8_t>(nz ? (sign ? -1 : 1) : 0);
+    for (int r = 0; r < kPackRecs; ++r) {
+        const int64_t ks = ks0 + r < KS ? ks0 + r : KS - 1;               // past the end: a duplicate, never stored
+        const uint8_t *rec = blob + kHeaderBytes + (rt * KS + ks) * kRecordBytes;
+#pragma unroll
+        for (int plane = 0; plane < 2; ++plane) w[r][plane] = load_global<uint32_t>(rec + plane * kPlaneBytes + 4 * t);
+    }
+#pragma unroll
+    for (int r = 0; r < kPackRecs; ++r) {
+        words[r][0][t] = w[r][0];
+        words[r][1][t] = w[r][1];
+    }
+    __syncthreads();
+    const int row = t >> 4, seg = t & 15;
+    const int f = seg >> 1, q0 = (seg & 1) * 2, i = f >> 1, par = f & 1;
+    const int64_t n = rt * kTileRows + row;
+    if (n >= N) return;
+#pragma unroll
+    for (int r = 0; r < kPackRecs; ++r) {
+        const int64_t k = (ks0 + r) * kStepK + seg * 16;
+        if (k >= K) break;
+#pragma unroll
+        for (int plane = 0; plane < 2; ++plane) {
+            int8_t *T = plane ? T2 : T1;
+            if (!T) continue;
+            const uint32_t wa = words[r][plane][(q0 * 16 + row) * 4 + i], wb = words[r][plane][((q0 + 1) * 16 + row) * 4 + i];
+            const uint32_t out[4] = {trits4(wa, par, 0), trits4(wa, par, 1), trits4(wb, par, 0), trits4(wb, par, 1)};
+            int8_t *dst = T + n * K + k;
+            if (VEC) *reinterpret_cast<uintx4 *>(dst) = uintx4{out[0], out[1], out[2], out[3]};
+            else {
+#pragma unroll
+                for (int b = 0; b < 16; ++b) dst[b] = static_cast<int8_t>((out[b >> 2] >> (8 * (b & 3))) & 0xffu);
+            }
+        }
     }
 }
 
@@ -1502,8 +1599,12 @@ ptqtp_status ptqtp_pack(const int8_t *T1, const int8_t *T2, const uint16_t *a1, 
         return PTQTP_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (dev_status) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, stream, dev_status);
-    hipLaunchKernelGGL(pack_kernel, dim3(static_cast<unsigned>(s.RT * s.KS)), dim3(576), 0, stream, T1, T2, a1, a2,
-                       static_cast<uint8_t *>(packed), s.N, s.K, s.RT, s.KS, s.NG, dev_status);
+    if (aligned(T1, 16) && aligned(T2, 16))
+        hipLaunchKernelGGL(pack_kernel<true>, dim3(static_cast<unsigned>(s.RT * ((s.KS + kPackRecs - 1) / kPackRecs))), dim3(256), 0, stream, T1, T2, a1,
+                           a2, static_cast<uint8_t *>(packed), s.N, s.K, s.RT, s.KS, s.NG, dev_status);
+    else
+        hipLaunchKernelGGL(pack_kernel<false>, dim3(static_cast<unsigned>(s.RT * ((s.KS + kPackRecs - 1) / kPackRecs))), dim3(256), 0, stream, T1, T2, a1,
+                           a2, static_cast<uint8_t *>(packed), s.N, s.K, s.RT, s.KS, s.NG, dev_status);
     return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
 
@@ -1518,10 +1619,13 @@ ptqtp_status ptqtp_unpack(const void *packed, int64_t M, int64_t N, int64_t K, i
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const uint8_t *blob = static_cast<const uint8_t *>(packed);
     if (T1 || T2) {
-        const int64_t blocks = (s.N * s.K + 255) / 256;
-        if (blocks > kMaxGrid) return PTQTP_ERR_SHAPE;
-        hipLaunchKernelGGL(unpack_trits_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream, blob, T1,
-                           T2, s.N, s.K, s.KS);
+        const int64_t blocks = s.RT * ((s.KS + kPackRecs - 1) / kPackRecs);
+        if (aligned(T1, 16) && aligned(T2, 16))
+            hipLaunchKernelGGL(unpack_trits_kernel<true>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
+                               blob, T1, T2, s.N, s.K, s.KS);
+        else
+            hipLaunchKernelGGL(unpack_trits_kernel<false>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
+                               blob, T1, T2, s.N, s.K, s.KS);
     }
     if (a1 || a2) {
         const int64_t blocks = (s.N * s.NG + 255) / 256;

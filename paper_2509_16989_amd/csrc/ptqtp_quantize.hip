@@ -9,10 +9,12 @@
 // ("Batch Processing").
 //
 // Mapping: 16 units per wave (four lanes x 32 elements per unit), state (trits) in HBM between iterations:
-// 6 bytes per weight per iteration (2 read for w, 2 read + 2 written for the trit pair), so an
-// iteration is HBM-bound like the forward path.  The sums S'S (small integers) and S'w (w * 2^24
-// is an integer: exact in 64-bit) are integer sums (32 per lane, then across the four lanes of the
-// unit); the 2x2 solve and the search
+// 6 bytes per weight per iteration (2 read for w, 2 read + 2 written for the trit pair).  The kernel is
+// bound by vector-ALU issue, not by that traffic: about 60 instructions per weight and iteration, of which
+// the nine-candidate search takes 43 (subtract, square, compare, minimum, select per candidate).
+// The sums S'S are small integers; S'w is summed in binary64, which is exact in any order here (every
+// term is a multiple of 2^-24 below 2^16 in magnitude), so it equals the integer sum an exact
+// implementation would form; the 2x2 solve and the search
 // run in binary64, one operation at a time with contraction off, so the integer decisions are
 // reproducible bit for bit.  The stopping rule needs a matrix-wide sum: every iteration is two
 // launches (units, then a fixed-order reduction that sets a device flag); later launches see the
@@ -31,13 +33,6 @@ struct QuantFlags {          // start of the workspace, 256 bytes
     int32_t iters;           // iterations performed so far
     int32_t pad[62];
 };
-
-__device__ __forceinline__ int64_t half_to_fixed24(uint32_t h) {       // w * 2^24, exact for finite w
-    const int e = (h >> 10) & 0x1f;
-    const int64_t frac = h & 0x3ff;
-    int64_t v = e == 0 ? frac : ((frac | 0x400) << (e - 1));
-    return (h & 0x8000u) ? -v : v;
-}
 
 __device__ __forceinline__ double half_to_double(uint32_t h) {
     return static_cast<double>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
@@ -78,15 +73,17 @@ __device__ __forceinline__ int quad_sum_i32(int v) {
     v += __shfl_xor(v, 2, 64);
     return v;
 }
-__device__ __forceinline__ int64_t quad_sum_i64(int64_t v) {
+__device__ __forceinline__ double quad_sum_f64(double v) {
 #pragma unroll
     for (int o = 1; o <= 2; o <<= 1) {
-        const int lo = __shfl_xor(static_cast<int>(v & 0xffffffff), o, 64);
-        const int hi = __shfl_xor(static_cast<int>(v >> 32), o, 64);
-        v += (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
+        const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+        const int lo = __shfl_xor(static_cast<int>(bits & 0xffffffffu), o, 64);
+        const int hi = __shfl_xor(static_cast<int>(bits >> 32), o, 64);
+        v = v + __builtin_bit_cast(double, (static_cast<uint64_t>(static_cast<uint32_t>(hi)) << 32) | static_cast<uint32_t>(lo));
     }
     return v;
 }
+
 
 // One iteration for every unit.  A wave holds 16 units: lane l works on elements (l%4)*32 .. +31 of
 // unit l/4, so the 2x2 solve (the same for all lanes of a unit) is repeated 4 times, not 64.
@@ -127,8 +124,10 @@ quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_
         lam = lambda[u]; ap1 = alpha[2 * u]; ap2 = alpha[2 * u + 1];
     }
 
+    // S'w in binary64 is exact in any order: every term t * w is a multiple of 2^-24 (w is binary16), and so
+    // is every partial sum, which stays below 128 * 65504 < 2^23: at most 47 significant bits.
     int s11 = 0, s22 = 0, s12 = 0;
-    int64_t B1 = 0, B2 = 0;
+    double b1 = 0.0, b2 = 0.0;
 #pragma unroll
     for (int e = 0; e < 32; ++e) {
         const uint32_t h = (wv[e >> 1] >> (16 * (e & 1))) & 0xffffu;
@@ -139,15 +138,15 @@ quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_
             t1 = static_cast<int8_t>((tv1[e >> 2] >> (8 * (e & 3))) & 0xffu);
             t2 = static_cast<int8_t>((tv2[e >> 2] >> (8 * (e & 3))) & 0xffu);
         }
-        const int64_t f = half_to_fixed24(h);
+        const double w = half_to_double(h);
         s11 += t1 * t1; s22 += t2 * t2; s12 += t1 * t2;
-        B1 += t1 * f; B2 += t2 * f;
+        b1 = __builtin_fma(static_cast<double>(t1), w, b1);          // exact, fused or not
+        b2 = __builtin_fma(static_cast<double>(t2), w, b2);
     }
     // S'S: three small integers in one word (unit sums are at most 128 in magnitude; s12 is signed)
     const int ps = quad_sum_i32(s11 | (s22 << 10) | ((s12 + 32) << 20));
     s11 = ps & 0x3ff; s22 = (ps >> 10) & 0x3ff; s12 = ((ps >> 20) & 0x3ff) - 128;
-    B1 = quad_sum_i64(B1); B2 = quad_sum_i64(B2);
-    const double b1 = static_cast<double>(B1) * 0x1p-24, b2 = static_cast<double>(B2) * 0x1p-24;   // exact
+    b1 = quad_sum_f64(b1); b2 = quad_sum_f64(b2);
 
     // ridge normal equations, closed-form inverse A^-1 = (1/det) adj(A), kappa = ||A||_F ||A^-1||_F
     const double A12 = static_cast<double>(s12);
@@ -187,31 +186,37 @@ quant_iter_kernel(const uint16_t *__restrict__ W, int8_t *__restrict__ T1, int8_
     const double a1 = m11 + m12, a2 = m21 + m22;
 
     // nine candidate values in the order c1 = -1,0,1 (outer), c2 = -1,0,1 (inner)
-    double cand[9];
+    // Candidate 8 - m is the exact negative of candidate m (negation commutes with every rounding), and
+    // w - (-v) is the same operation as w + v: five values are kept, four of them used with either sign.
+    double cand[5];
 #pragma unroll
-    for (int c1 = -1; c1 <= 1; ++c1)
-#pragma unroll
-        for (int c2 = -1; c2 <= 1; ++c2) cand[(c1 + 1) * 3 + (c2 + 1)] = static_cast<double>(c1) * a1 + static_cast<double>(c2) * a2;
+    for (int m = 0; m < 5; ++m) cand[m] = static_cast<double>(m / 3 - 1) * a1 + static_cast<double>(m % 3 - 1) * a2;
+    // Per element: the first minimum of the nine errors.  The winner is tracked as the byte pair it will be
+    // stored as (c1 in bits 0..7, c2 in bits 8..15); four elements' pairs are then split into one word per plane.
     uint32_t o1[8], o2[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { o1[i] = 0; o2[i] = 0; }
+    for (int q = 0; q < 8; ++q) {
+        uint32_t pair[4];
 #pragma unroll
-    for (int e = 0; e < 32; ++e) {
-        const double w = half_to_double((wv[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-        double best = __builtin_inf();
-        int bm = 0;
+        for (int i = 0; i < 4; ++i) {
+            const int e = 4 * q + i;
+            const double w = half_to_double((wv[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+            const double d0 = w - cand[0];
+            double best = d0 * d0;
+            uint32_t code = 0xffffu;                                   // (-1, -1)
 #pragma unroll
-        for (int m = 0; m < 9; ++m) {
-            const double d = w - cand[m];
-            const double err = d * d;
-            if (err < best) { best = err; bm = m; }
+            for (int m = 1; m < 9; ++m) {
+                const double d = m < 5 ? w - cand[m] : w + cand[8 - m];
+                const double err = d * d;
+                const uint32_t cm = (static_cast<uint32_t>(m / 3 - 1) & 0xffu) | ((static_cast<uint32_t>(m % 3 - 1) & 0xffu) << 8);
+                code = err < best ? cm : code;
+                best = __builtin_fmin(best, err);
+            }
+            pair[i] = code;
         }
-        // bm -> (c1, c2) as bytes: c1 = bm/3 - 1, c2 = bm%3 - 1
-        const int c1 = (bm >= 6) - (bm < 3);
-        const int r3 = bm - 3 * (c1 + 1);
-        const int c2 = r3 - 1;
-        o1[e >> 2] |= (static_cast<uint32_t>(c1) & 0xffu) << (8 * (e & 3));
-        o2[e >> 2] |= (static_cast<uint32_t>(c2) & 0xffu) << (8 * (e & 3));
+        const uint32_t p01 = pair[0] | (pair[1] << 16), p23 = pair[2] | (pair[3] << 16);
+        o1[q] = __builtin_amdgcn_perm(p23, p01, 0x06040200u);          // bytes 0, 2 of each pair word
+        o2[q] = __builtin_amdgcn_perm(p23, p01, 0x07050301u);          // bytes 1, 3
     }
     if (valid) {
 #pragma unroll

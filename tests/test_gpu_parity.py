@@ -63,6 +63,32 @@ def test_pack_unpack_roundtrip(ptq, N, K):
     assert np.array_equal(a2.cpu().numpy().view(np.uint16), lin["a2"].view(np.uint16))
 
 
+@pytest.mark.parametrize("N,K", [(48, 384), (257, 1024)])
+def test_pack_unpack_planes_not_16_byte_aligned(ptq, N, K):
+    """Planes that start 2 bytes into an allocation take the byte-wise path: same blob, same planes back."""
+    lin = workloads.make_linear(N, K, 53, N, K)
+    ref = pack(ptq, lin)
+    bufs = []
+    for name in ("T1", "T2"):
+        buf = torch.zeros(N * K + 16, dtype=torch.int8, device="cuda:0")
+        buf[2:2 + N * K] = dev(lin[name]).reshape(-1)
+        bufs.append(buf)
+    views = [b[2:2 + N * K].reshape(N, K) for b in bufs]
+    assert all(v.data_ptr() % 16 == 2 for v in views)
+    packed = ptq.ptqtp_pack(views[0], views[1], dev(lin["a1"]), dev(lin["a2"]))
+    assert torch.equal(packed, ref)
+    outs = [torch.full((N * K + 16,), 7, dtype=torch.int8, device="cuda:0") for _ in range(2)]
+    from paper_2509_16989_amd import binding
+    st = binding.raw().ptqtp_unpack(packed.data_ptr(), 1, N, K, 128, outs[0].data_ptr() + 2, outs[1].data_ptr() + 2, None, None,
+                                torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    torch.cuda.synchronize()
+    for out, name in zip(outs, ("T1", "T2")):
+        got = out.cpu().numpy()
+        assert np.array_equal(got[2:2 + N * K].reshape(N, K), lin[name])
+        assert np.all(got[:2] == 7) and np.all(got[2 + N * K:] == 7)            # nothing outside the planes
+
+
 def test_pack_payload_matches_memory_model(ptq):
     # appendix memory model: 4.25 bits per weight at G = 128
     for N, K in [(1024, 1024), (4096, 4096), (4096, 14336)]:
@@ -80,8 +106,16 @@ def test_pack_agrees_with_canonical_storage(ptq):
 def test_pack_flags_bad_trit(ptq):
     lin = workloads.make_linear(32, 256, 52)
     lin["T2"][5, 77] = 2
+    lin["T1"][31, 255] = -128
+    lin["T1"][0, 3] = 127
     with pytest.raises(ValueError):
         pack(ptq, lin)
+    # the blob is still written: the offending entries as 0, their neighbours untouched
+    packed = ptq.ptqtp_pack(dev(lin["T1"]), dev(lin["T2"]), dev(lin["a1"]), dev(lin["a2"]), check=False)
+    T1, T2, _, _ = ptq.ptqtp_unpack(packed, 32, 256)
+    want1, want2 = lin["T1"].copy(), lin["T2"].copy()
+    want2[5, 77] = 0; want1[31, 255] = 0; want1[0, 3] = 0
+    assert np.array_equal(T1.cpu().numpy(), want1) and np.array_equal(T2.cpu().numpy(), want2)
 
 
 # ---------------------------------------------------------------- gemv, batch 1
