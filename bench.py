@@ -257,7 +257,8 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
     (M = 128, 512) on the small MFMA tiles;
     70B shapes at M = 1 and 32 (hot: one copy) and prefill M = 2048 on the MFMA tiles;
     the whole stack in one launch at M = 4, 16, 64; the dependent decode chain;
-    plus the quantizer (ptqtp_quantize) on two 8B shapes, with the oracle quantizer timed on a 256 x 4096 sample."""
+    plus the quantizer (ptqtp_quantize) on two 8B shapes, with the oracle quantizer timed on a 256 x 4096 sample,
+    and ptqtp_pack / ptqtp_unpack on an 8B and a 70B shape."""
     import workloads
     res = {"8b": {}, "70b": {}}
     dev = xs[0].device
@@ -345,6 +346,32 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
             it = int(out[4].item())
             res["quantize"][f"{name}_{n}x{k}"] = {"ms": round(dt * 1e3, 2), "iters": it, "us_per_iter": round(dt * 1e6 / it, 1),
                                                   "state_GBps": round(6.0 * n * k * it / dt / 1e9, 1)}
+        # the step between quantizer and path: ptqtp_pack / ptqtp_unpack on random planes (2 B of int8 + 0.53 B of
+        # records per weight, one side read, the other written)
+        res["pack"] = {}
+        from paper_2509_16989_amd import binding
+        lib = binding.raw()
+        for n, k in ((4096, 4096), (28672, 8192)):
+            T1 = torch.randint(-1, 2, (n, k), device=dev, dtype=torch.int8)
+            T2 = torch.randint(-1, 2, (n, k), device=dev, dtype=torch.int8)
+            a1 = torch.rand(n, k // 128, device=dev).half()
+            a2 = torch.rand(n, k // 128, device=dev).half()
+            blob = ptq.ptqtp_pack(T1, T2, a1, a2, check=False)
+            o1, o2 = torch.empty_like(T1), torch.empty_like(T2)
+            nb = blob.numel()
+            calls = {"pack": lambda: lib.ptqtp_pack(T1.data_ptr(), T2.data_ptr(), a1.data_ptr(), a2.data_ptr(), 1, n, k, 128,
+                                                    blob.data_ptr(), nb, None, stream.cuda_stream),
+                     "unpack": lambda: lib.ptqtp_unpack(blob.data_ptr(), 1, n, k, 128, o1.data_ptr(), o2.data_ptr(), None, None,
+                                                        stream.cuda_stream)}
+            entry = {}
+            for what, call in calls.items():
+                us = _graph_time(torch, stream, lambda: [call() for _ in range(4)], 4, reps=3 if quick else 10)
+                entry[what + "_us"] = round(us, 1)
+                entry[what + "_GBps"] = round((2 * n * k + nb) / us / 1e3, 1)
+            assert torch.equal(o1, T1) and torch.equal(o2, T2)
+            res["pack"][f"{n}x{k}"] = entry
+            del T1, T2, o1, o2, blob
+        note("pack done")
     if not no_cpu:
         import numpy as np
         import oracle

@@ -83,7 +83,8 @@ size_t ptqtp_workspace_bytes(int64_t M, int64_t N, int64_t K, int32_t group);
  * Pack two trit planes and their scales into the device layout the compute
  * kernels stream (appendix memory model: 2-bit trits, fp16 scales).
  *
- *   T1, T2      device, int8 [N, K] row-major, entries in {-1,0,+1}
+ *   T1, T2      device, int8 [N, K] row-major, entries in {-1,0,+1}; 2-byte alignment is
+ *               enough, planes that are both 16-byte aligned are read 16 bytes at a time
  *   a1, a2      device, fp16 bit patterns [N, K/group] row-major
  *   packed      device, receives ptqtp_packed_bytes(M,N,K,group) bytes; opaque
  *   dev_status  device int32 or NULL; set to 0, then to 1 by the kernel if any
@@ -99,7 +100,8 @@ ptqtp_status ptqtp_pack(const int8_t *T1, const int8_t *T2,
 /*
  * Inverse of ptqtp_pack (bit-exact): recovers T1, T2 (int8 [N,K]) and a1, a2
  * (fp16 bits [N,K/group]) from a blob.  All pointers device.  Any of the four
- * outputs may be NULL to skip it.
+ * outputs may be NULL to skip it.  Planes that are both 16-byte aligned are written 16
+ * bytes at a time, others byte by byte.
  */
 ptqtp_status ptqtp_unpack(const void *packed, int64_t M, int64_t N, int64_t K, int32_t group,
                           int8_t *T1, int8_t *T2, uint16_t *a1, uint16_t *a2, void *stream);

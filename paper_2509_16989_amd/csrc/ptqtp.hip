@@ -1599,12 +1599,13 @@ ptqtp_status ptqtp_pack(const int8_t *T1, const int8_t *T2, const uint16_t *a1, 
         return PTQTP_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (dev_status) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, stream, dev_status);
+    const dim3 grid(static_cast<unsigned>(s.RT * ((s.KS + kPackRecs - 1) / kPackRecs)));
     if (aligned(T1, 16) && aligned(T2, 16))
-        hipLaunchKernelGGL(pack_kernel<true>, dim3(static_cast<unsigned>(s.RT * ((s.KS + kPackRecs - 1) / kPackRecs))), dim3(256), 0, stream, T1, T2, a1,
-                           a2, static_cast<uint8_t *>(packed), s.N, s.K, s.RT, s.KS, s.NG, dev_status);
+        hipLaunchKernelGGL(pack_kernel<true>, grid, dim3(256), 0, stream, T1, T2, a1, a2,
+                           static_cast<uint8_t *>(packed), s.N, s.K, s.RT, s.KS, s.NG, dev_status);
     else
-        hipLaunchKernelGGL(pack_kernel<false>, dim3(static_cast<unsigned>(s.RT * ((s.KS + kPackRecs - 1) / kPackRecs))), dim3(256), 0, stream, T1, T2, a1,
-                           a2, static_cast<uint8_t *>(packed), s.N, s.K, s.RT, s.KS, s.NG, dev_status);
+        hipLaunchKernelGGL(pack_kernel<false>, grid, dim3(256), 0, stream, T1, T2, a1, a2,
+                           static_cast<uint8_t *>(packed), s.N, s.K, s.RT, s.KS, s.NG, dev_status);
     return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
 
