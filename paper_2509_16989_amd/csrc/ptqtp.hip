@@ -31,7 +31,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
+#include <algorithm>
 #include <type_traits>
+#include <vector>
 
 #include "ptqtp.h"
 #include "ptqtp_device.hpp"
@@ -1705,16 +1707,22 @@ ptqtp_status ptqtp_gemv_batch_plan(const ptqtp_linear *linears, int32_t count, i
             return PTQTP_ERR_ALIGN;
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    // The table lists the linears with the longest rows first (stable otherwise): a workgroup's work grows with K,
+    // and the launch ends sooner when the items handed out last are the short ones.
+    std::vector<int> order(count);
+    for (int i = 0; i < count; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return linears[a].K > linears[b].K; });
     int64_t first = 0;
     for (int base = 0; base < count; base += kPlanChunk) {
         DescChunk chunk = {};
         const int n = count - base < kPlanChunk ? count - base : kPlanChunk;
         for (int i = 0; i < n; ++i) {
+            const ptqtp_linear &lin = linears[order[base + i]];
             Shape s;
-            make_shape(1, linears[base + i].N, linears[base + i].K, group, &s, &st);
+            make_shape(1, lin.N, lin.K, group, &s, &st);
             LinearDesc &d = chunk.d[i];
-            d.records = static_cast<const uint8_t *>(linears[base + i].packed) + kHeaderBytes;
-            d.x = linears[base + i].x; d.y = linears[base + i].y;
+            d.records = static_cast<const uint8_t *>(lin.packed) + kHeaderBytes;
+            d.x = lin.x; d.y = lin.y;
             d.N = static_cast<int32_t>(s.N); d.K = static_cast<int32_t>(s.K);
             d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
             d.first_item = static_cast<int32_t>(first); d.pad = 0;
