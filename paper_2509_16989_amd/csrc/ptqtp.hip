@@ -467,7 +467,7 @@ __device__ __forceinline__ int slot_rd_off(int nl, int q, int f) { return nl * k
 // PLAN: the item list of a batch plan (R must be 1): one launch over many linears, all with M tokens.
 // ML = load instructions per 16-token tile (1, 2, 4 or 8): covers M <= 2*ML when MT == 1.
 template <int MT, int R, int S, bool PLAN, int ML>
-__global__ void __launch_bounds__(MT * R >= 8 ? 256 : 512)
+__global__ void __launch_bounds__(MT * R >= 6 ? 256 : 512)
 gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict__ records_,
                   const uint16_t *__restrict__ x_, void *__restrict__ y_, int M, int N_, int K_, int RT_, int KS_,
                   int y_f16_, const uint16_t *__restrict__ residual, int gated)
@@ -1089,13 +1089,13 @@ double best_tile_cost(int row_tiles, int M)
 }
 
 // The small-batch kernel on chunks of 64 tokens, in microseconds: a full chunk streams the packed rows once (0.037 per
-// row tile and 32 groups, at least 11 for the launch and its ramp); a last chunk of up to 16 / 32 tokens uses the narrower kernels.
+// row tile and 32 groups, at least 11 for the launch and its ramp); a last chunk of up to 16 / 32 / 48 tokens uses the narrower kernels.
 double small_cost(int row_tiles, int groups, int M)
 {
     const double stream = 0.037 * row_tiles * groups / 32.0;
     const double full = stream > 11.0 ? stream : 11.0;
     const int rest = M % 64;
-    return (M / 64) * full + (rest == 0 ? 0.0 : rest > 32 ? full : rest > 16 ? 0.6 * full : 0.4 * full);
+    return (M / 64) * full + (rest == 0 ? 0.0 : rest > 48 ? full : rest > 32 ? 0.8 * full : rest > 16 ? 0.6 * full : 0.4 * full);
 }
 
 // Launch tile kind k over row tiles rt0 .. rt1-1 (rt0 a multiple of 16; rt1 < 0: to the end, else a multiple of 16).
@@ -1165,8 +1165,8 @@ hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y,
 {
     // measured: 8 waves per item, except for the register-heavy 64-token x 2-tile case: 2 waves there on 8B shapes
     // (K = 4096), 4 on longer rows (70B down, K = 28672, at 64 tokens: 166 -> 105 us)
-    int W = g_tune_small_waves > 0 ? g_tune_small_waves : (MT * R >= 8 ? (s.KS > 16 ? 4 : 2) : 8);
-    if (W > (MT * R >= 8 ? 4 : 8)) W = MT * R >= 8 ? 4 : 8;
+    int W = g_tune_small_waves > 0 ? g_tune_small_waves : (MT * R >= 6 ? (s.KS > 16 ? 4 : 2) : 8);
+    if (W > (MT * R >= 6 ? 4 : 8)) W = MT * R >= 6 ? 4 : 8;
     while (W > 1 && W > s.KS) W /= 2;
     const int64_t grid = gated ? s.RT / 2 : (s.RT + R - 1) / R;
     return launch_gemm_items_ml<MT, R, S, false>(nullptr, records, x, y, M, static_cast<int>(s.N), static_cast<int>(s.K),
@@ -1180,6 +1180,7 @@ hipError_t launch_gemm_items_plan(const PlanHeader *plan, int64_t items, int M, 
     const int W = g_tune_small_waves > 0 ? (g_tune_small_waves > 8 ? 8 : g_tune_small_waves) : 4;
     if (M <= 16) return launch_gemm_items_ml<1, 1, 2, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
     if (M <= 32) return launch_gemm_items_ml<2, 1, 1, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
+    if (M <= 48) return launch_gemm_items_ml<3, 1, 1, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
     return launch_gemm_items_ml<4, 1, 1, true>(plan, nullptr, nullptr, nullptr, M, 0, 0, 0, 0, 0, items, W, stream);
 }
 
@@ -1423,6 +1424,8 @@ hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int 
                                : launch_gemm_items<1, 1, 2>(records, x, y, M, s, f16, stream, residual, gated);
     if (M <= 32) return R == 2 ? launch_gemm_items<2, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
                                : launch_gemm_items<2, 1, 1>(records, x, y, M, s, f16, stream, residual, gated);
+    if (M <= 48) return R == 2 ? launch_gemm_items<3, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
+                               : launch_gemm_items<3, 1, 1>(records, x, y, M, s, f16, stream, residual, gated);
     return R == 2 ? launch_gemm_items<4, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
                   : launch_gemm_items<4, 1, 1>(records, x, y, M, s, f16, stream, residual, gated);
 }
@@ -1772,6 +1775,9 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
         else if (M <= 32) e = rows == 1 ? launch_gemm_rows<2, 1, false>(ph, items, Mi, stream)
                             : fold ? launch_gemm_rows<2, 2, true>(ph, items, Mi, stream)
                                    : launch_gemm_rows<2, 2, false>(ph, items, Mi, stream);
+        else if (M <= 48) e = rows == 1 ? launch_gemm_rows<3, 1, false>(ph, items, Mi, stream)
+                            : fold ? launch_gemm_rows<3, 2, true>(ph, items, Mi, stream)
+                                   : launch_gemm_rows<3, 2, false>(ph, items, Mi, stream);
         else e = rows == 1 ? launch_gemm_rows<4, 1, false>(ph, items, Mi, stream)
                  : fold ? launch_gemm_rows<4, 2, true>(ph, items, Mi, stream)
                         : launch_gemm_rows<4, 2, false>(ph, items, Mi, stream);
