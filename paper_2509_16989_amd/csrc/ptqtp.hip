@@ -294,6 +294,7 @@ struct PlanHeader {           // 64 bytes, followed by LinearDesc[count], then i
 };
 constexpr uint64_t kPlanMagic = 0x314e4c5050545150ull;  // "PQTPPLN1"
 constexpr int kPlanChunk = 32;
+constexpr int kPlanPad = 16;     // items per linear are rounded up to this: a workgroup of up to 16 row tiles never straddles two linears
 
 struct DescChunk { LinearDesc d[kPlanChunk]; };
 
@@ -1193,7 +1194,7 @@ hipError_t launch_gemm_items_plan(const PlanHeader *plan, int64_t items, int M, 
 // activation traffic through L1 is a quarter of the per-wave scheme and no cross-wave reduction
 // is needed: each wave stores its own 16 rows.  Needs four row tiles of the same linear per
 // workgroup (eight when a wave owns two), which batch plans guarantee (items are padded to a
-// multiple of eight per linear).
+// multiple of sixteen per linear).
 //
 // FOLD: the group scale is multiplied into the expanded trits before the matrix pipe
 // (alpha * {0,+-1} is exact in fp16 and alpha*t*x is exact in fp32), so both planes and all
@@ -1683,7 +1684,7 @@ static ptqtp_status plan_items(const ptqtp_linear *linears, int32_t count, int32
         Shape s;
         ptqtp_status st;
         if (!make_shape(1, linears[i].N, linears[i].K, group, &s, &st)) return st;
-        *total += (s.RT + 7) / 8 * 8;          // every linear starts a new group of eight items
+        *total += (s.RT + kPlanPad - 1) / kPlanPad * kPlanPad;   // every linear starts a new group of kPlanPad items
     }
     return *total > (1ll << 30) ? PTQTP_ERR_SHAPE : PTQTP_OK;
 }
@@ -1730,7 +1731,7 @@ ptqtp_status ptqtp_gemv_batch_plan(const ptqtp_linear *linears, int32_t count, i
             d.N = static_cast<int32_t>(s.N); d.K = static_cast<int32_t>(s.K);
             d.RT = static_cast<int32_t>(s.RT); d.KS = static_cast<int32_t>(s.KS);
             d.first_item = static_cast<int32_t>(first); d.pad = 0;
-            first += (s.RT + 7) / 8 * 8;
+            first += (s.RT + kPlanPad - 1) / kPlanPad * kPlanPad;
         }
         hipLaunchKernelGGL(plan_write_kernel, dim3(1), dim3(64), 0, stream, static_cast<PlanHeader *>(plan), chunk,
                            base, n, count, static_cast<int>(total), y_dtype == PTQTP_F16 ? 1 : 0);
@@ -1767,9 +1768,13 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
     hipError_t e;
     if (g_tune_small_rows_kernel == 0) e = launch_gemm_items_plan(ph, items, Mi, stream);
     else {
-        const int rows = g_tune_small_rows ? g_tune_small_rows : 2;
+        // measured on the 8B stack: four row tiles per wave (16 per workgroup share one activation tile) up to 16
+        // tokens (M = 16: 727 -> 677 us), two above (four measured 6 % slower at 17..32 tokens)
+        const int rows = g_tune_small_rows ? g_tune_small_rows : (M <= 16 ? 4 : 2);
         const bool fold = g_tune_small_fold < 0 ? M > 32 : g_tune_small_fold != 0;   // measured on the 8B stack
-        if (M <= 16) e = rows == 1 ? launch_gemm_rows<1, 1, false>(ph, items, Mi, stream)
+        if (M <= 16 && rows == 4) e = launch_gemm_rows<1, 4, false>(ph, items, Mi, stream);
+        else if (M <= 32 && rows == 4) e = launch_gemm_rows<2, 4, false>(ph, items, Mi, stream);
+        else if (M <= 16) e = rows == 1 ? launch_gemm_rows<1, 1, false>(ph, items, Mi, stream)
                        : fold ? launch_gemm_rows<1, 2, true>(ph, items, Mi, stream)
                               : launch_gemm_rows<1, 2, false>(ph, items, Mi, stream);
         else if (M <= 32) e = rows == 1 ? launch_gemm_rows<2, 1, false>(ph, items, Mi, stream)
@@ -1823,7 +1828,7 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
         return PTQTP_OK;
     }
     if (!strcmp(key, "small_rows")) {
-        if (value < 0 || value > 2) return PTQTP_ERR_SHAPE;
+        if (value < 0 || value > 4 || value == 3) return PTQTP_ERR_SHAPE;
         g_tune_small_rows = value;
         return PTQTP_OK;
     }

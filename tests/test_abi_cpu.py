@@ -59,7 +59,7 @@ def test_batch_plan_validation(lib):
     arr[0] = _Linear(0x10000, 0x20000, 0x30000, 4096, 4096)
     arr[1] = _Linear(0x10000, 0x20000, 0x30000, 1000, 1024)
     arr[2] = _Linear(0x10000, 0x20000, 0x30000, 16, 128)
-    items = 256 + 64 + 8            # ceil(N/16) per entry, rounded up to a multiple of eight
+    items = 256 + 64 + 16           # ceil(N/16) per entry, rounded up to a multiple of sixteen
     assert lib.ptqtp_batch_items(arr, 3, 128) == items
     assert lib.ptqtp_batch_plan_bytes(arr, 3, 128) == 64 + 3 * 48 + 4 * items
     assert lib.ptqtp_batch_items(arr, 0, 128) == 0
