@@ -1769,11 +1769,14 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
     if (g_tune_small_rows_kernel == 0) e = launch_gemm_items_plan(ph, items, Mi, stream);
     else {
         // measured on the 8B stack: four row tiles per wave (16 per workgroup share one activation tile) up to 16
-        // tokens (M = 16: 727 -> 677 us), two above (four measured 6 % slower at 17..32 tokens)
-        const int rows = g_tune_small_rows ? g_tune_small_rows : (M <= 16 ? 4 : 2);
+        // tokens (M = 16: 727 -> 677 us) and from 33 on (M = 64: 1665 -> 1536 us), two at 17..32 (four: 3-6 % slower)
+        const int rows = g_tune_small_rows ? g_tune_small_rows : (M <= 16 || M > 32 ? 4 : 2);
         const bool fold = g_tune_small_fold < 0 ? M > 32 : g_tune_small_fold != 0;   // measured on the 8B stack
         if (M <= 16 && rows == 4) e = launch_gemm_rows<1, 4, false>(ph, items, Mi, stream);
-        else if (M <= 32 && rows == 4) e = launch_gemm_rows<2, 4, false>(ph, items, Mi, stream);
+        else if (M <= 32 && rows == 4) e = fold ? launch_gemm_rows<2, 4, true>(ph, items, Mi, stream)
+                                                : launch_gemm_rows<2, 4, false>(ph, items, Mi, stream);
+        else if (M <= 48 && rows == 4) e = launch_gemm_rows<3, 4, true>(ph, items, Mi, stream);
+        else if (rows == 4) e = launch_gemm_rows<4, 4, true>(ph, items, Mi, stream);
         else if (M <= 16) e = rows == 1 ? launch_gemm_rows<1, 1, false>(ph, items, Mi, stream)
                        : fold ? launch_gemm_rows<1, 2, true>(ph, items, Mi, stream)
                               : launch_gemm_rows<1, 2, false>(ph, items, Mi, stream);
