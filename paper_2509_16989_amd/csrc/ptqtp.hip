@@ -1416,14 +1416,19 @@ hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int 
                         hipStream_t stream, const uint16_t *residual = nullptr, int gated = 0)
 {
     // measured on 8B shapes: two row tiles per item (sharing one set of activation operands) when the layer has
-    // many row tiles, and always for 17..32 tokens; one otherwise
+    // many row tiles, and always for 17..32 tokens; one otherwise (R = 4 exists for up to 32 tokens)
     int R = s.RT >= 512 ? 2 : 1;
     if (M > 16 && M <= 32) R = 2;
+    // four on the widest layers, where items are plentiful and the activations re-read per item weigh most
+    // (70B gate, 28672 rows: 16 tokens 31.8 -> 29.7 us, 32 tokens 53 -> 44 us; slower on every narrower layer)
+    if (s.RT >= 1536 && M >= 16 && M <= 32) R = 4;
     if (g_tune_small_rows > 0) R = g_tune_small_rows;
     if (gated) R = 2;                                  // a (gate tile, up tile) pair per item
-    if (M <= 16) return R == 2 ? launch_gemm_items<1, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
+    if (M <= 16) return R == 4 ? launch_gemm_items<1, 4, 1>(records, x, y, M, s, f16, stream, residual, gated)
+                      : R == 2 ? launch_gemm_items<1, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
                                : launch_gemm_items<1, 1, 2>(records, x, y, M, s, f16, stream, residual, gated);
-    if (M <= 32) return R == 2 ? launch_gemm_items<2, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
+    if (M <= 32) return R == 4 ? launch_gemm_items<2, 4, 1>(records, x, y, M, s, f16, stream, residual, gated)
+                      : R == 2 ? launch_gemm_items<2, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
                                : launch_gemm_items<2, 1, 1>(records, x, y, M, s, f16, stream, residual, gated);
     if (M <= 48) return R == 2 ? launch_gemm_items<3, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
                                : launch_gemm_items<3, 1, 1>(records, x, y, M, s, f16, stream, residual, gated);

@@ -373,19 +373,20 @@ def test_gemm_small_batches(ptq, M):
     check(y, lin, x)
 
 
-@pytest.mark.parametrize("N,K,M", [(1000, 1024, 4), (257, 4096, 16), (48, 384, 64), (16, 128, 3), (96, 14336, 24)])
+@pytest.mark.parametrize("N,K,M", [(1000, 1024, 4), (257, 4096, 16), (48, 384, 64), (16, 128, 3), (96, 14336, 24),
+                                    (24583, 256, 16), (24700, 384, 20), (24576, 128, 32)])   # last three: 4 row tiles per item
 def test_gemm_small_shapes(ptq, N, K, M):
     lin = workloads.make_linear(N, K, 61, N, K)
     x = workloads.make_x(M, K, 61, N, M)
     check(ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K), lin, x)
 
 
-@pytest.mark.parametrize("rows,waves", [(1, 1), (1, 8), (2, 2), (2, 4), (2, 8)])
+@pytest.mark.parametrize("rows,waves", [(1, 1), (1, 8), (2, 2), (2, 4), (2, 8), (4, 1), (4, 4), (4, 8)])
 def test_gemm_small_launch_shapes(ptq, rows, waves):
     try:
         ptq.ptqtp_tune("small_rows", rows)
         ptq.ptqtp_tune("small_waves", waves)
-        for N, K, M in [(200, 2304, 9), (1000, 640, 33), (48, 4096, 64), (8200, 256, 5)]:
+        for N, K, M in [(200, 2304, 9), (1000, 640, 33), (48, 4096, 64), (8200, 256, 5), (1000, 640, 20)]:
             lin = workloads.make_linear(N, K, 65, N)
             x = workloads.make_x(M, K, 65, N)
             check(ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K), lin, x)
