@@ -1217,8 +1217,8 @@ __device__ __forceinline__ constexpr int rows_operand_offset(int mt, int f) {
     return (mt >> 1) * (16 * kRowsChunk<MT>) + (mt & 1) * 512 + f * 64;
 }
 
-template <int MT, int RTW, bool FOLD>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((!FOLD && MT * RTW >= 8) ? 1 : 2)))
+template <int MT, int RTW, bool FOLD, int NW = 4>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((!FOLD && MT * RTW >= 8) ? 1 : 2)))
 gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
 {
     extern __shared__ char xtile[];                  // [2][(MT+1)/2 blocks of 32 tokens][16 chunks]
@@ -1226,7 +1226,7 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nl = lane & 15, q = lane >> 4;
-    const int item0 = blockIdx.x * (4 * RTW);
+    const int item0 = blockIdx.x * (NW * RTW);
     if (item0 >= plan->total_items) return;
     const LinearDesc *table = reinterpret_cast<const LinearDesc *>(plan + 1);
     const int32_t *map = reinterpret_cast<const int32_t *>(table + plan->count);
@@ -1337,15 +1337,16 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
             }
         }
     };
-    // staging role: wave w brings in chunks w, w+4, ... of the step; lane t*32+p: piece p of token c + 16*t
+    // staging role: wave w brings in chunks w, w+NW, ... of the step; lane t*32+p: piece p of token c + 16*t
     auto stage_direct = [&](int ks, int buf) {
         constexpr int NCH = 16 * ((MT + 1) / 2);
+        static_assert(NCH % NW == 0, "the chunks of a step divide among the waves");
         int kc = ks * kStepK + (lane & 31) * 8;
         kc = kc < K ? kc : kc - 128;                 // padded half record: its trits are zero
         if (MT > 1 || lane < 32) {                   // 16 tokens or fewer: the second token of a chunk does not exist
 #pragma unroll
-            for (int j = 0; j < NCH / 4; ++j) {
-                const int c = w + 4 * j;             // chunk of the step
+            for (int j = 0; j < NCH / NW; ++j) {
+                const int c = w + NW * j;            // chunk of the step
                 int m = (c >> 4) * 32 + (c & 15) + (lane >> 5) * 16;
                 m = m < M ? m : M - 1;               // rows past M: duplicates, never stored
                 asm volatile("" : "+v"(m));          // keep the row address out of loop-invariant registers
@@ -1395,19 +1396,20 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
     }
 }
 
-template <int MT, int RTW, bool FOLD>
+template <int MT, int RTW, bool FOLD, int NW = 4>
 hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStream_t stream)
 {
+    static_assert(NW * RTW <= kPlanPad, "a workgroup's row tiles belong to one linear");
     const size_t lds = 2 * static_cast<size_t>((MT + 1) / 2) * 16 * kRowsChunk<MT>;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW, FOLD>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW, FOLD, NW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((gemm_rows_kernel<MT, RTW, FOLD>), dim3(static_cast<unsigned>((items + 4 * RTW - 1) / (4 * RTW))),
-                       dim3(256), lds, stream, plan, M);
+    hipLaunchKernelGGL((gemm_rows_kernel<MT, RTW, FOLD, NW>), dim3(static_cast<unsigned>((items + NW * RTW - 1) / (NW * RTW))),
+                       dim3(64 * NW), lds, stream, plan, M);
     return hipGetLastError();
 }
 
@@ -1773,11 +1775,20 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
     hipError_t e;
     if (g_tune_small_rows_kernel == 0) e = launch_gemm_items_plan(ph, items, Mi, stream);
     else {
-        // measured on the 8B stack: four row tiles per wave (16 per workgroup share one activation tile) up to 16
-        // tokens (M = 16: 727 -> 677 us) and from 33 on (M = 64: 1665 -> 1536 us), two at 17..32 (four: 3-6 % slower)
-        const int rows = g_tune_small_rows ? g_tune_small_rows : (M <= 16 || M > 32 ? 4 : 2);
+        // 16 row tiles per workgroup share one activation tile.  Measured on the 8B stack: as four waves x four
+        // row tiles up to 16 tokens (M = 16: 727 us with 8 per workgroup -> 677 us), as eight waves x two above
+        // (M = 32: 950 -> 925 us, M = 64: 1665 us with 8 per workgroup -> 1536 us as 4 x 4 -> 1450 us as 8 x 2).
+        // `rows`: 1, 2, 4 = row tiles per wave of a four-wave workgroup; 8 = two per wave, eight waves.
+        const int rows = g_tune_small_rows ? g_tune_small_rows : (M <= 16 ? 4 : 8);
         const bool fold = g_tune_small_fold < 0 ? M > 32 : g_tune_small_fold != 0;   // measured on the 8B stack
-        if (M <= 16 && rows == 4) e = launch_gemm_rows<1, 4, false>(ph, items, Mi, stream);
+        if (rows == 8) {
+            if (M <= 16) e = launch_gemm_rows<1, 2, false, 8>(ph, items, Mi, stream);
+            else if (M <= 32) e = fold ? launch_gemm_rows<2, 2, true, 8>(ph, items, Mi, stream)
+                                       : launch_gemm_rows<2, 2, false, 8>(ph, items, Mi, stream);
+            else if (M <= 48) e = launch_gemm_rows<3, 2, true, 8>(ph, items, Mi, stream);
+            else e = launch_gemm_rows<4, 2, true, 8>(ph, items, Mi, stream);
+        }
+        else if (M <= 16 && rows == 4) e = launch_gemm_rows<1, 4, false>(ph, items, Mi, stream);
         else if (M <= 32 && rows == 4) e = fold ? launch_gemm_rows<2, 4, true>(ph, items, Mi, stream)
                                                 : launch_gemm_rows<2, 4, false>(ph, items, Mi, stream);
         else if (M <= 48 && rows == 4) e = launch_gemm_rows<3, 4, true>(ph, items, Mi, stream);
@@ -1836,7 +1847,7 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
         return PTQTP_OK;
     }
     if (!strcmp(key, "small_rows")) {
-        if (value < 0 || value > 4 || value == 3) return PTQTP_ERR_SHAPE;
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return PTQTP_ERR_SHAPE;
         g_tune_small_rows = value;
         return PTQTP_OK;
     }

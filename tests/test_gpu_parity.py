@@ -202,7 +202,7 @@ def test_gemm_batch_matches_oracle(ptq, M):
         entries.append((pack(ptq, lin), dev(x), y, N, K))
     plan = ptq.ptqtp_gemv_batch_plan(entries)
     # shared activation tile (1 or 2 row tiles per wave; scales applied after or before the matrix pipe), per-wave loads
-    for kernel, rows, fold in ((-1, 0, -1), (-1, 1, -1), (-1, 2, 0), (-1, 2, 1), (-1, 4, 0), (-1, 4, 1), (0, 0, -1)):
+    for kernel, rows, fold in ((-1, 0, -1), (-1, 1, -1), (-1, 2, 0), (-1, 2, 1), (-1, 4, 0), (-1, 4, 1), (-1, 8, 0), (-1, 8, 1), (0, 0, -1)):
         try:
             ptq.ptqtp_tune("batch_rows_kernel", kernel)
             ptq.ptqtp_tune("small_rows", rows)
