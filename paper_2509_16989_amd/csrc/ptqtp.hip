@@ -1186,15 +1186,15 @@ hipError_t launch_gemm_items_plan(const PlanHeader *plan, int64_t items, int M, 
 }
 
 // ------------------------------------------------------------------------------------------
-// small-batch kernel for batched launches: workgroup = four row tiles sharing one activation tile
+// small-batch kernel for batched launches: workgroup = NW waves x RTW row tiles sharing one activation tile
 // ------------------------------------------------------------------------------------------
-// Wave w owns row tile 4*group + w over the whole K; per 256-column step the workgroup loads the
-// step's activations once (MT*16 tokens x 512 B into a double-buffered LDS tile; one barrier per
-// step) and every wave reads its MFMA A operands from there, so the
-// activation traffic through L1 is a quarter of the per-wave scheme and no cross-wave reduction
-// is needed: each wave stores its own 16 rows.  Needs four row tiles of the same linear per
-// workgroup (eight when a wave owns two), which batch plans guarantee (items are padded to a
-// multiple of sixteen per linear).
+// Wave w owns the RTW consecutive row tiles from NW*RTW*group + w*RTW over the whole K; per 256-column
+// step the workgroup loads the step's activations once (MT*16 tokens x 512 B into a double-buffered LDS
+// tile; one barrier per step) and every wave reads its MFMA A operands from there, so a linear's
+// activations cross from L2 into the CU once per NW*RTW row tiles (with per-item loads that traffic
+// exceeds the weight bytes from 8 tokens on) and no cross-wave reduction is needed: each wave stores its
+// own rows.  Needs NW*RTW <= 16 row tiles of the same linear per workgroup, which batch plans guarantee
+// (items are padded to a multiple of sixteen per linear).
 //
 // FOLD: the group scale is multiplied into the expanded trits before the matrix pipe
 // (alpha * {0,+-1} is exact in fp16 and alpha*t*x is exact in fp32), so both planes and all
