@@ -141,7 +141,7 @@ pack_kernel(const int8_t *__restrict__ T1, const int8_t *__restrict__ T2,
             v[r][plane] = uintx4{0u, 0u, 0u, 0u};
             if (n < N && k < K) {
                 const int8_t *src = (plane ? T2 : T1) + n * K + k;
-                if (VEC) v[r][plane] = load_global<uintx4>(src);
+                if (VEC) v[r][plane] = load_stream<uintx4>(src);      // read once: keep it out of the caches' way
                 else {
                     uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
