@@ -290,7 +290,8 @@ ptqtp_status ptqtp_gemm_route(int64_t M, int64_t N, int64_t K, int32_t group, in
  * "stream_depth" (batch 1: records in flight per wave: 1, 2 or 4), "small_waves" (one linear at batch > 1:
  * waves per item, 1..8), "small_rows" (row tiles per item / per wave of the small-batch kernels: 1 or 2, for ptqtp_gemm_batch also 4, and 8 = two per wave in a workgroup of eight waves),
  * "chain_waves" (ptqtp_chain_run: waves per item, an even number up to 16), "chain_depth" (ptqtp_chain_run:
- * records in flight per wave: 1, 2 or 4), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation loads, -1/1 = shared activation tile),
+ * records in flight per wave: 1, 2 or 4), "chain_table" (ptqtp_chain_run: 1 = every level looks its stages up in the
+ * device-side plan, 0 = default: levels of up to four stages carry their descriptors as kernel arguments), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation loads, -1/1 = shared activation tile),
  * "small_fold" (ptqtp_gemm_batch with two row tiles per wave: 1 = multiply the group scales into the
  * expanded trits before the matrix pipe, 0 = rescale the per-group sums after it, -1 = default: before for
  * more than 32 tokens), "tile" (1 = use an MFMA tile for every batch > 1, -1 = never below 256 tokens,

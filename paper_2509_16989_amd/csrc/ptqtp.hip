@@ -39,7 +39,7 @@
 #include "ptqtp_device.hpp"
 
 namespace ptqtp_detail {
-extern int g_chain_waves, g_chain_depth;       // ptqtp_chain.hip
+extern int g_chain_waves, g_chain_depth, g_chain_table;       // ptqtp_chain.hip
 }
 
 namespace {
@@ -1819,6 +1819,11 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!strcmp(key, "chain_depth")) {
         if (value != 0 && value != 1 && value != 2 && value != 4) return PTQTP_ERR_SHAPE;
         ptqtp_detail::g_chain_depth = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "chain_table")) {
+        if (value < 0 || value > 1) return PTQTP_ERR_SHAPE;
+        ptqtp_detail::g_chain_table = value;
         return PTQTP_OK;
     }
     if (!strcmp(key, "small_fold")) {

@@ -10,12 +10,14 @@
 // every record of the level is requested in one round trip.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <vector>
 
 #include "ptqtp.h"
 #include "ptqtp_device.hpp"
 
 namespace ptqtp_detail {
 int g_chain_waves = 0, g_chain_depth = 0;      // ptqtp_tune("chain_waves" / "chain_depth"): 0 = heuristic
+int g_chain_table = 0;                         // ptqtp_tune("chain_table"): 1 = every level finds its stages through the plan table
 // ptqtp.hip: the small-batch item kernel with a stage's epilogue in its final reduction
 hipError_t small_batch_stage(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual, int M,
                              int64_t N, int64_t K, int y_f16, int gated, hipStream_t stream);
@@ -83,33 +85,23 @@ __global__ void __launch_bounds__(256) chain_map_kernel(ChainHeader *plan)
     }
 }
 
-// S = records a wave requests at once; the workgroup has blockDim.x / 64 <= 16 waves (an even
-// number, so that a gated-MLP item gives each of its two row tiles half of them).
+// One work item: S = records a wave requests at once; the workgroup has blockDim.x / 64 <= 16 waves (an even
+// number, so that a gated-MLP item gives each of its two row tiles half of them).  Every argument is uniform over
+// the workgroup (it comes from kernel arguments or from the plan table through scalar loads).
 template <int S>
-__global__ void __launch_bounds__(kChainMaxWaves * 64)
-chain_items_kernel(const ChainHeader *__restrict__ plan, int item_base)
+__device__ __forceinline__ void chain_item(const uint8_t *records, const uint16_t *x, void *y, const uint16_t *residual,
+                                           int N, int K, int KS, int RT, int it, bool pair, int y_f16,
+                                           float (*red)[16], uintx2 (*xs)[64])
 {
-    __shared__ float red[kChainMaxWaves][16];
-    __shared__ uintx2 xs[kChainMaxWaves][64];
-
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int W = blockDim.x >> 6;
     const int nl = lane & 15, q = lane >> 4;
-    const int item = item_base + static_cast<int>(blockIdx.x);     // the grid is exactly the level's items
-
-    const StageDesc *table = chain_table(plan);
-    const int32_t *map = reinterpret_cast<const int32_t *>(table + plan->count);
-    const StageDesc *sd = table + map[item];
-    const int K = sd->K, KS = sd->KS, N = sd->N;
-    const bool pair = sd->epilogue == PTQTP_EPI_SWIGLU;
     const int Wh = pair ? W / 2 : W;                    // waves that share one row tile
     const int half = w / Wh, part = w - half * Wh;
-    const int it = item - sd->first_item;
-    const int rt = it + (half ? sd->RT / 2 : 0);
-    const uint8_t *rec0 = sd->records + static_cast<size_t>(rt) * KS * kRecordBytes;
+    const int rt = it + (half ? RT / 2 : 0);
+    const uint8_t *rec0 = records + static_cast<size_t>(rt) * KS * kRecordBytes;
     const int rot = (it * 5) % KS;
-    const uint16_t *x = sd->x;
 
     uintx4 xa[1][8];
 #pragma unroll
@@ -172,23 +164,65 @@ chain_items_kernel(const ChainHeader *__restrict__ plan, int item_base)
             for (int ww = 0; ww < W / 2; ++ww) { lo += red[ww][nl]; hi += red[W / 2 + ww][nl]; }
             if (pair) out = (lo / (1.0f + __expf(-lo))) * hi;     // silu(gate) * up
             else out = lo + hi;
-            if (sd->residual != nullptr && n < n_out) out += half_bits_to_float(load_global<uint16_t>(sd->residual + n));
+            if (residual != nullptr && n < n_out) out += half_bits_to_float(load_global<uint16_t>(residual + n));
         }
-        if (sd->y_f16) {
+        if (y_f16) {
             const uint32_t hb = __builtin_bit_cast(uint16_t, static_cast<_Float16>(out));
             const uint32_t nb = __shfl_down(hb, 1);                 // the odd neighbour's half
             if (lane < 16 && (lane & 1) == 0 && n < n_out) {
-                uint16_t *yp = reinterpret_cast<uint16_t *>(sd->y) + n;
+                uint16_t *yp = reinterpret_cast<uint16_t *>(y) + n;
                 if (n + 1 < n_out) *reinterpret_cast<uint32_t *>(yp) = hb | (nb << 16);
                 else *yp = static_cast<uint16_t>(hb);             // last element of an odd-length output
             }
         } else if (lane < 16 && n < n_out) {
-            reinterpret_cast<float *>(sd->y)[n] = out;
+            reinterpret_cast<float *>(y)[n] = out;
         }
     }
 }
 
-struct LevelRange { int first_item, items, min_steps, gated; };   // min_steps: fewest 256-column steps of a stage of the level; gated: it has a gated stage
+// A level of up to kLevelStages stages: the stage descriptors travel as kernel arguments, so a workgroup knows its
+// records' address without a single load from memory (a level's launch is short: two or three dependent loads from
+// a device-side table before the first record request were a third of it).  The grid is exactly the level's items;
+// first_item counts from the launch's first item.
+constexpr int kLevelStages = 4;
+struct LevelArgs { StageDesc d[kLevelStages]; };
+
+template <int S, bool MULTI>
+__global__ void __launch_bounds__(kChainMaxWaves * 64)
+chain_level_kernel(const LevelArgs args, int n_stages)
+{
+    __shared__ float red[kChainMaxWaves][16];
+    __shared__ uintx2 xs[kChainMaxWaves][64];
+    const int item = static_cast<int>(blockIdx.x);
+    int idx = 0;
+    if (MULTI) {
+#pragma unroll
+        for (int i = 1; i < kLevelStages; ++i)
+            if (i < n_stages && item >= args.d[i].first_item) idx = i;
+    }
+    const StageDesc &sd = args.d[idx];
+    chain_item<S>(sd.records, sd.x, sd.y, sd.residual, sd.N, sd.K, sd.KS, sd.RT, item - sd.first_item,
+                  sd.epilogue == PTQTP_EPI_SWIGLU, sd.y_f16, red, xs);
+}
+
+// The same items found through the device-side plan (item -> stage map): for levels of more than kLevelStages stages.
+template <int S>
+__global__ void __launch_bounds__(kChainMaxWaves * 64)
+chain_items_kernel(const ChainHeader *__restrict__ plan, int item_base)
+{
+    __shared__ float red[kChainMaxWaves][16];
+    __shared__ uintx2 xs[kChainMaxWaves][64];
+    const int item = item_base + static_cast<int>(blockIdx.x);     // the grid is exactly the level's items
+    const StageDesc *table = chain_table(plan);
+    const int32_t *map = reinterpret_cast<const int32_t *>(table + plan->count);
+    const StageDesc *sd = table + map[item];
+    chain_item<S>(sd->records, sd->x, sd->y, sd->residual, sd->N, sd->K, sd->KS, sd->RT, item - sd->first_item,
+                  sd->epilogue == PTQTP_EPI_SWIGLU, sd->y_f16, red, xs);
+}
+
+// first_stage / stages: the level's slice of the stage array; min_steps / max_steps: fewest and most 256-column steps
+// of a stage of the level; gated: it has a gated stage
+struct LevelRange { int first_item, items, min_steps, max_steps, gated, first_stage, stages; };
 
 // host-side geometry of a chain; returns false (and a status) on invalid input
 bool chain_geometry(const ptqtp_stage *stages, int32_t count, int32_t group, StageDesc *descs /* count or null */,
@@ -217,7 +251,10 @@ bool chain_geometry(const ptqtp_stage *stages, int32_t count, int32_t group, Sta
             if (lv >= 0 && levels) levels[lv].items = cur_level_items;
             ++lv;
             cur_level_items = 0;
-            if (levels) { levels[lv].first_item = static_cast<int>(item); levels[lv].min_steps = 1 << 30; levels[lv].gated = 0; }
+            if (levels) {
+                levels[lv].first_item = static_cast<int>(item); levels[lv].min_steps = 1 << 30; levels[lv].max_steps = 0;
+                levels[lv].gated = 0; levels[lv].first_stage = i; levels[lv].stages = 0;
+            }
             prev_level = s.level;
         }
         const int64_t RT = (s.N + kTileRows - 1) / kTileRows;
@@ -235,6 +272,8 @@ bool chain_geometry(const ptqtp_stage *stages, int32_t count, int32_t group, Sta
             descs[i] = d;
         }
         if (levels && KS < levels[lv].min_steps) levels[lv].min_steps = static_cast<int>(KS);
+        if (levels && KS > levels[lv].max_steps) levels[lv].max_steps = static_cast<int>(KS);
+        if (levels) ++levels[lv].stages;
         if (levels && s.epilogue == PTQTP_EPI_SWIGLU) levels[lv].gated = 1;
         item += items;
         cur_level_items += static_cast<int>(items);
@@ -244,6 +283,35 @@ bool chain_geometry(const ptqtp_stage *stages, int32_t count, int32_t group, Sta
     *n_levels = lv + 1;
     *total_items = item;
     return true;
+}
+
+// launch shape of a level: W waves per item, S records in flight per wave
+void level_shape(const LevelRange &lr, int *W_, int *S_) {
+    // thousands of items: 4 waves x 2 records each keep the stream full.  Few items: more waves per
+    // item and one record each put the whole level in flight in one round trip.
+    int W = 4, S = 2;
+    if (lr.items < 2048) {
+        S = 1;
+        while (W < kChainMaxWaves && lr.items * W * 2 <= 4096) W *= 2;
+        if (lr.gated) {
+            // a gated item gives each of its two row tiles half of the waves: double them, and let a wave that still
+            // has four or more steps request two at a time (measured on the 8B gate|up stage: 16.3 -> 14.4 us)
+            if (W < kChainMaxWaves) W *= 2;
+            if ((lr.min_steps + W / 2 - 1) / (W / 2) >= 4) S = 2;
+        }
+        while (W > 2 && W / 2 > lr.min_steps) W /= 2;
+    }
+    if (ptqtp_detail::g_chain_waves > 0) W = ptqtp_detail::g_chain_waves;
+    if (ptqtp_detail::g_chain_depth > 0) S = ptqtp_detail::g_chain_depth;
+    *W_ = W; *S_ = S >= 4 ? 4 : S == 2 ? 2 : 1;
+}
+
+template <bool MULTI>
+void launch_level(const LevelArgs &args, int n, int items, int W, int S, hipStream_t stream) {
+    const dim3 grid(static_cast<unsigned>(items)), block(W * 64);
+    if (S == 4) hipLaunchKernelGGL((chain_level_kernel<4, MULTI>), grid, block, 0, stream, args, n);
+    else if (S == 2) hipLaunchKernelGGL((chain_level_kernel<2, MULTI>), grid, block, 0, stream, args, n);
+    else hipLaunchKernelGGL((chain_level_kernel<1, MULTI>), grid, block, 0, stream, args, n);
 }
 
 }  // namespace
@@ -261,9 +329,10 @@ ptqtp_status ptqtp_chain_plan(const ptqtp_stage *stages, int32_t count, int32_t 
                               void *plan, size_t plan_bytes, void *stream_) {
     if (!plan) return PTQTP_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(plan) & 255) return PTQTP_ERR_ALIGN;
-    static thread_local StageDesc descs[PTQTP_CHAIN_MAX_STAGES];
     int n_levels; int64_t total; ptqtp_status st;
-    if (!chain_geometry(stages, count, group, descs, nullptr, &n_levels, &total, &st)) return st;
+    if (!chain_geometry(stages, count, group, nullptr, nullptr, &n_levels, &total, &st)) return st;
+    std::vector<StageDesc> descs(static_cast<size_t>(count));       // host memory only
+    chain_geometry(stages, count, group, descs.data(), nullptr, &n_levels, &total, &st);
     if (plan_bytes < ptqtp_chain_plan_bytes(stages, count, group)) return PTQTP_ERR_SIZE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     ChainHeader *ph = static_cast<ChainHeader *>(plan);
@@ -282,32 +351,32 @@ ptqtp_status ptqtp_chain_plan(const ptqtp_stage *stages, int32_t count, int32_t 
 ptqtp_status ptqtp_chain_run(const ptqtp_stage *stages, int32_t count, int32_t group, const void *plan, void *stream_) {
     if (!plan) return PTQTP_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(plan) & 255) return PTQTP_ERR_ALIGN;
-    static thread_local LevelRange lr[PTQTP_CHAIN_MAX_STAGES];
     int n_levels; int64_t total; ptqtp_status st;
-    if (!chain_geometry(stages, count, group, nullptr, lr, &n_levels, &total, &st)) return st;
+    if (!chain_geometry(stages, count, group, nullptr, nullptr, &n_levels, &total, &st)) return st;
+    std::vector<StageDesc> descs(static_cast<size_t>(count));       // host memory only
+    std::vector<LevelRange> lr(static_cast<size_t>(count));
+    chain_geometry(stages, count, group, descs.data(), lr.data(), &n_levels, &total, &st);
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const ChainHeader *ph = static_cast<const ChainHeader *>(plan);
     for (int l = 0; l < n_levels; ++l) {
-        // thousands of items: 4 waves x 2 records each keep the stream full.  Few items: more waves per
-        // item and one record each put the whole level in flight in one round trip.
-        int W = 4, S = 2;
-        if (lr[l].items < 2048) {
-            S = 1;
-            while (W < kChainMaxWaves && lr[l].items * W * 2 <= 4096) W *= 2;
-            if (lr[l].gated) {
-                // a gated item gives each of its two row tiles half of the waves: double them, and let a wave that still
-                // has four or more steps request two at a time (measured on the 8B gate|up stage: 16.3 -> 14.4 us)
-                if (W < kChainMaxWaves) W *= 2;
-                if ((lr[l].min_steps + W / 2 - 1) / (W / 2) >= 4) S = 2;
+        int W, S;
+        level_shape(lr[l], &W, &S);
+        if (lr[l].stages <= kLevelStages && ptqtp_detail::g_chain_table <= 0) {
+            // the usual case: the level's descriptors fit the kernel arguments
+            LevelArgs args = {};
+            for (int i = 0; i < lr[l].stages; ++i) {
+                args.d[i] = descs[static_cast<size_t>(lr[l].first_stage + i)];
+                args.d[i].first_item -= lr[l].first_item;
             }
-            while (W > 2 && W / 2 > lr[l].min_steps) W /= 2;
+            if (lr[l].stages == 1) launch_level<false>(args, 1, lr[l].items, W, S, stream);
+            else launch_level<true>(args, lr[l].stages, lr[l].items, W, S, stream);
+        } else {
+            // a wide level: items find their stage through the device-side plan
+            const dim3 grid(static_cast<unsigned>(lr[l].items)), block(W * 64);
+            if (S == 4) hipLaunchKernelGGL((chain_items_kernel<4>), grid, block, 0, stream, ph, lr[l].first_item);
+            else if (S == 2) hipLaunchKernelGGL((chain_items_kernel<2>), grid, block, 0, stream, ph, lr[l].first_item);
+            else hipLaunchKernelGGL((chain_items_kernel<1>), grid, block, 0, stream, ph, lr[l].first_item);
         }
-        if (ptqtp_detail::g_chain_waves > 0) W = ptqtp_detail::g_chain_waves;
-        if (ptqtp_detail::g_chain_depth > 0) S = ptqtp_detail::g_chain_depth;
-        const dim3 grid(static_cast<unsigned>(lr[l].items)), block(W * 64);
-        if (S >= 4) hipLaunchKernelGGL((chain_items_kernel<4>), grid, block, 0, stream, ph, lr[l].first_item);
-        else if (S == 2) hipLaunchKernelGGL((chain_items_kernel<2>), grid, block, 0, stream, ph, lr[l].first_item);
-        else hipLaunchKernelGGL((chain_items_kernel<1>), grid, block, 0, stream, ph, lr[l].first_item);
     }
     return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }

@@ -27,17 +27,32 @@ def test_algorithmic_bytes_follow_the_memory_model():
     assert bench.algorithmic_bytes(N, K, 16) == planes_and_scales + 16 * (2 * K + 4 * N)
 
 
-def test_recorded_traffic_comes_from_the_committed_profile():
+def test_recorded_traffic_comes_from_the_committed_profile(monkeypatch):
     import bench
-    t = bench.recorded_traffic("batch", 32)
-    assert isinstance(t, int) and t > 0
-    # the counters saw within 2 % of the algorithmic bytes of the default workload
     import workloads
+    profile = os.path.join(ROOT, "profiles", "gemv_items_batch_8b_stack.txt")
+    named = [l.split(":")[1].split()[0] for l in open(profile) if l.startswith("kernel_source_hash:")]
+    assert len(named) == 1
+    # handed out only while the library's sources hash to what the summary names ...
+    monkeypatch.setattr(bench, "kernel_source_hash", lambda: named[0])
+    r = bench.recorded_traffic("batch", 32)
+    assert isinstance(r["traffic"], int) and "not measured by this run" in r["traffic_source"]
+    # ... the counters saw within 2 % of the algorithmic bytes of the default workload
     algo = 32 * sum(bench.algorithmic_bytes(*workloads.SHAPES_8B[n]) for n in workloads.LINEAR_ORDER)
-    assert 0.98 < t / algo < 1.02
-    # any other launch mode or stack depth has no recorded figure
-    assert bench.recorded_traffic("graph", 32) is None
-    assert bench.recorded_traffic("batch", 8) is None
+    assert 0.98 < r["traffic"] / algo < 1.02
+    # any other launch mode or stack depth has no recorded figure, nor has a library whose sources have changed
+    assert bench.recorded_traffic("graph", 32)["traffic"] is None
+    assert bench.recorded_traffic("batch", 8)["traffic"] is None
+    monkeypatch.setattr(bench, "kernel_source_hash", lambda: "0" * 16)
+    assert bench.recorded_traffic("batch", 32) == {"traffic": None, "traffic_source": None}
+
+
+def test_per_config_entries_name_the_binding_roof():
+    import bench
+    e = bench.roof_entry(10.0, [(4096, 4096)], 16)
+    assert e["bound"] == "hbm" and abs(e["frac"] - bench.algorithmic_bytes(4096, 4096, 16) / 10.0 / 1e3 / 8000.0) < 1e-4
+    e = bench.roof_entry(1000.0, [(8192, 28672)], 2048)
+    assert e["bound"] == "mfma" and abs(e["frac"] - 4.0 * 2048 * 8192 * 28672 / 1000.0 / 1e6 / 2500.0) < 1e-4
 
 
 def test_product_fails_loudly_without_its_library(tmp_path, monkeypatch):

@@ -310,3 +310,156 @@ def test_chain_batch_dependent_stack(ptq, M):
     for lin, xin, yout, res, epi in lins:
         check_stage(yout, lin, xin.cpu().numpy(), epi, None if res is None else res.cpu().numpy())
     assert not torch.equal(lins[-1][2], lins[-1][3])
+
+
+# ---------------------------------------------------------------- every launch shape of the batch-1 chain kernel
+@pytest.mark.parametrize("depth", [1, 2, 4])
+@pytest.mark.parametrize("waves", [2, 4, 8, 16])
+def test_chain_forced_launch_shapes(ptq, waves, depth):
+    # waves per item x records in flight per wave, forced through the tuning hook, on plain and gated stages:
+    # an odd number of groups (K = 640: the last record is half padding), a ragged last row tile (N = 200),
+    # rows long enough for several rounds of the K loop (K = 4224), fp16 and fp32 stores, with and without residual
+    cases = [(200, 640, "none", True, torch.float16), (200, 640, "none", False, torch.float32),
+             (40, 4224, "none", True, torch.float32), (960, 640, "swiglu", False, torch.float16),
+             (64, 4224, "swiglu", True, torch.float32), (2048, 1024, "swiglu", True, torch.float16)]
+    try:
+        ptq.ptqtp_tune("chain_waves", waves)
+        ptq.ptqtp_tune("chain_depth", depth)
+        for N, K, epi, res, ydt in cases:
+            lin = workloads.make_linear(N, K, 91, N, K)
+            x = workloads.make_x(1, K, 91, N)[0]
+            n_out = N // 2 if epi == "swiglu" else N
+            r = workloads.make_x(1, n_out, 91, N, 7)[0] if res else None
+            y = torch.full((n_out,), float("nan"), dtype=ydt, device="cuda:0")
+            plan = ptq.ptqtp_chain_plan([dict(packed=pack(ptq, lin), x=dev(x), y=y, N=N, K=K, level=0,
+                                              residual=dev(r) if res else None,
+                                              epilogue=ptq.PTQTP_EPI_SWIGLU if epi == "swiglu" else ptq.PTQTP_EPI_NONE)])
+            run_chain(ptq, plan)
+            check_stage(y, lin, x, epi, r)
+    finally:
+        ptq.ptqtp_tune("chain_waves", 0)
+        ptq.ptqtp_tune("chain_depth", 0)
+
+
+def test_chain_forced_launch_shapes_agree_bitwise_on_integer_inputs(ptq):
+    # integer-exact inputs: every launch shape must give the same bits (any summation order is exact)
+    N, K = 96, 2304
+    lin, x = workloads.integer_exact_case(N, K, 1, 92)
+    blob, xd = pack(ptq, lin), dev(x[0])
+    outs = []
+    try:
+        for waves in (2, 4, 8, 16):
+            for depth in (1, 2, 4):
+                ptq.ptqtp_tune("chain_waves", waves)
+                ptq.ptqtp_tune("chain_depth", depth)
+                y = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda:0")
+                run_chain(ptq, ptq.ptqtp_chain_plan([dict(packed=blob, x=xd, y=y, N=N, K=K, level=0)]))
+                outs.append(y)
+    finally:
+        ptq.ptqtp_tune("chain_waves", 0)
+        ptq.ptqtp_tune("chain_depth", 0)
+    ref, _ = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
+    for y in outs:
+        assert np.array_equal(y.cpu().numpy().astype(np.float64), ref[0])
+
+
+# ---------------------------------------------------------------- the 8B chain exactly as bench.py times it
+def _fused_host_linear(names, layer, scale=None):
+    """Host copy of what bench.build_decode_chain packs for one stage: the named linears' rows stacked, the
+    scales multiplied by `scale` in binary16 (one rounding, as the device multiply does)."""
+    parts = [workloads.linear_8b(nm, layer) for nm in names]
+    lin = {k: np.concatenate([p[k] for p in parts]) for k in ("T1", "T2", "a1", "a2")}
+    if scale is not None:
+        lin["a1"] = (lin["a1"] * np.float16(scale)).astype(np.float16)
+        lin["a2"] = (lin["a2"] * np.float16(scale)).astype(np.float16)
+    lin["N"], lin["K"] = lin["T1"].shape
+    return lin
+
+
+def test_chain_full_8b_stack_as_benchmarked_sampled(ptq):
+    # the dependent decode step bench.py reports: 32 layers x {qkv, o, gate|up, down} at the 8B shapes, built by the
+    # benchmark's own builder, run eagerly and replayed from a hipGraph as it is timed.  Layers 0 and 31: every stage
+    # on sampled rows against the oracle fed the fp16 input the GPU gave that stage; all layers: outputs finite and
+    # the replay bit-identical to the eager run.
+    import bench
+    dev0 = torch.device("cuda:0")
+    blobs, xs, ys, jobs, dims, _ = bench.build_stack(ptq, torch, workloads, 32, dev0, log=False)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        stages, x0, _ = bench.build_decode_chain(ptq, torch, blobs, jobs, dims)
+        del blobs, xs, ys
+        assert len(stages) == 128
+        plan = ptq.ptqtp_chain_plan(stages)
+        for st in stages:
+            st["y"].fill_(float("nan"))
+        ptq.ptqtp_chain_run(plan)
+        stream.synchronize()
+        eager = [st["y"].clone() for st in stages]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            ptq.ptqtp_chain_run(plan)
+        for st in stages:
+            st["y"].fill_(float("nan"))
+        g.replay()
+        stream.synchronize()
+    for st, e in zip(stages, eager):
+        assert bool(torch.isfinite(st["y"].float()).all())
+        assert torch.equal(st["y"], e)
+    rng = np.random.default_rng(8)
+    spec = [(("q", "k", "v"), None, "none"), (("o",), bench.CHAIN_O_SCALE, "none"),
+            (("gate", "up"), None, "swiglu"), (("down",), bench.CHAIN_DOWN_SCALE, "none")]
+    for layer in (0, 31):
+        for s, (names, scale, epi) in enumerate(spec):
+            st = stages[4 * layer + s]
+            lin = _fused_host_linear(names, layer, scale)
+            N, K = lin["N"], lin["K"]
+            assert (N, K) == (st["N"], st["K"])
+            # the packed stage holds exactly these planes and scales (bit-exact, whole matrix)
+            t1, t2, s1, s2 = ptq.ptqtp_unpack(st["packed"], N, K)
+            assert np.array_equal(t1.cpu().numpy(), lin["T1"]) and np.array_equal(t2.cpu().numpy(), lin["T2"])
+            assert np.array_equal(s1.cpu().numpy().view(np.uint16), lin["a1"].view(np.uint16))
+            assert np.array_equal(s2.cpu().numpy().view(np.uint16), lin["a2"].view(np.uint16))
+            del t1, t2, s1, s2
+            n_out = N // 2 if epi == "swiglu" else N
+            rows = np.unique(np.concatenate([np.arange(0, 16), np.arange(n_out - 16, n_out), rng.integers(0, n_out, 256)]))
+            sel = np.concatenate([rows, n_out + rows]) if epi == "swiglu" else rows
+            sub = {k: lin[k][sel] for k in ("T1", "T2", "a1", "a2")}
+            sub["N"], sub["K"] = len(sel), K
+            x16 = st["x"].cpu().numpy()[:K]
+            r16 = None if st["residual"] is None else st["residual"].cpu().numpy()[rows]
+            check_stage(st["y"][torch.from_numpy(rows).to(dev0)], sub, x16, epi, r16)
+
+
+def test_chain_wide_level_and_table_lookup(ptq):
+    # a level of six independent stages (more than travel as kernel arguments: the items find their stage through the
+    # device-side plan), followed by a dependent level of two; then the same chain with every level forced through
+    # the plan table -- bit-identical, and both against the oracle
+    H = 256
+    x = workloads.make_x(1, H, 93, 1)[0]
+    xd = dev(x)
+    sizes = (64, 48, 256, 16, 100, 32)
+    parts = [workloads.make_linear(n, H, 93, i) for i, n in enumerate(sizes)]
+    outs = [torch.full((p["N"],), float("nan"), dtype=torch.float16, device="cuda:0") for p in parts]
+    o = workloads.make_linear(H, H, 93, 9)
+    g = workloads.make_linear(128, H, 93, 10)
+    yo = torch.full((H,), float("nan"), dtype=torch.float32, device="cuda:0")
+    yg = torch.full((64,), float("nan"), dtype=torch.float16, device="cuda:0")
+    stages = [dict(packed=pack(ptq, p), x=xd, y=y, N=p["N"], K=H, level=0) for p, y in zip(parts, outs)]
+    stages.append(dict(packed=pack(ptq, o), x=outs[2], y=yo, N=H, K=H, level=1, residual=xd))
+    stages.append(dict(packed=pack(ptq, g), x=outs[2], y=yg, N=128, K=H, level=1, epilogue=ptq.PTQTP_EPI_SWIGLU))
+    plan = ptq.ptqtp_chain_plan(stages)
+    run_chain(ptq, plan)
+    first = [t.clone() for t in outs + [yo, yg]]
+    for p, y in zip(parts, outs):
+        check_stage(y, p, x, "none", None)
+    check_stage(yo, o, outs[2].cpu().numpy(), "none", x)
+    check_stage(yg, g, outs[2].cpu().numpy(), "swiglu", None)
+    for t in outs + [yo, yg]:
+        t.fill_(float("nan"))
+    try:
+        ptq.ptqtp_tune("chain_table", 1)
+        run_chain(ptq, plan)
+    finally:
+        ptq.ptqtp_tune("chain_table", 0)
+    for a, b in zip(first, outs + [yo, yg]):
+        assert torch.equal(a, b)

@@ -681,18 +681,22 @@ def test_gemm_small_8b_q_sampled(ptq, M):
     _sampled_rows_check(ptq, lin, x, y, rows)
 
 
-def test_gemv_70b_shapes_sampled(ptq):
-    for name in ("k", "down"):
-        lin = workloads.linear_70b(name)
-        N, K = lin["N"], lin["K"]
-        x = workloads.x_for(name, 1, K, config=4)
-        y = ptq.ptqtp_gemv(pack(ptq, lin), dev(x).reshape(-1), N, K)
-        rows = np.unique(np.random.default_rng(3).integers(0, N, 256))
-        _sampled_rows_check(ptq, lin, x, y, rows)
-        if name == "down":
-            x32 = workloads.x_for(name, 32, K, config=4)
-            y32 = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x32), N, K)
-            _sampled_rows_check(ptq, lin, x32, y32, rows[:64])
+@pytest.mark.parametrize("name", ["q", "k", "gate", "down"])
+def test_gemv_70b_shapes_sampled(ptq, name):
+    # every 70B shape at batch 1 (streamed rows) and at 32 tokens (small-batch kernel), sampled rows
+    lin = workloads.linear_70b(name)
+    N, K = lin["N"], lin["K"]
+    packed = pack(ptq, lin)
+    x = workloads.x_for(name, 1, K, config=4)
+    y = ptq.ptqtp_gemv(packed, dev(x).reshape(-1), N, K)
+    rows = np.unique(np.concatenate([np.arange(0, 16), np.arange(N - 16, N), np.random.default_rng(3).integers(0, N, 256)]))
+    _sampled_rows_check(ptq, lin, x, y, rows)
+    x32 = workloads.x_for(name, 32, K, config=4)
+    y32 = ptq.ptqtp_gemm_small(packed, dev(x32), N, K)
+    assert ptq.ptqtp_gemm_route(32, N, K)[0] == ptq.PTQTP_ROUTE_SMALL
+    _sampled_rows_check(ptq, lin, x32, y32, rows[:96])
+    y32b = ptq.ptqtp_gemm(packed, dev(x32), N, K)                 # the dispatching entry point takes the same route
+    assert torch.equal(y32b, y32)
 
 
 @pytest.mark.parametrize("N,K", [(262144, 128), (16, 262144), (1, 128), (100000, 384)])
