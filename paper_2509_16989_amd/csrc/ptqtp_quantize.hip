@@ -327,19 +327,11 @@ size_t ptqtp_quantize_workspace_bytes(int64_t N, int64_t K, int32_t group) {
     return sizeof(QuantFlags) + units * 4 * sizeof(double);      // alpha (2), lambda, delta2
 }
 
-ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t group, int32_t max_iters, double eps,
-                            int8_t *T1, int8_t *T2, uint16_t *a1, uint16_t *a2, int32_t *iters, void *workspace,
-                            size_t workspace_bytes, void *stream_)
+// The decomposition itself, enqueued on `stream_` with its state in `workspace` (validated by the callers).
+static ptqtp_status quantize_enqueue(const uint16_t *W, int64_t N, int64_t K, int32_t group, int32_t max_iters, double eps,
+                                     int8_t *T1, int8_t *T2, uint16_t *a1, uint16_t *a2, int32_t *iters, void *workspace,
+                                     void *stream_)
 {
-    if (!W || !T1 || !T2 || !a1 || !a2 || !workspace) return PTQTP_ERR_NULL;
-    if (group != kGroup) return PTQTP_ERR_GROUP;
-    if (!quantize_shape_ok(N, K, group) || max_iters < 0 || max_iters > 10000 || !(eps >= 0.0))
-        return PTQTP_ERR_SHAPE;
-    const size_t need = ptqtp_quantize_workspace_bytes(N, K, group);
-    if (workspace_bytes < need) return PTQTP_ERR_SIZE;
-    if (!aligned(workspace, 256) || !aligned(W, 16) || !aligned(T1, 16) || !aligned(T2, 16) || !aligned(a1, 2) ||
-        !aligned(a2, 2))
-        return PTQTP_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const int64_t NG = K / group, units = N * NG;
     QuantFlags *flags = static_cast<QuantFlags *>(workspace);
@@ -365,6 +357,30 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
     hipLaunchKernelGGL(quant_finish_kernel, dim3(static_cast<unsigned>((units + 255) / 256)), dim3(256), 0, stream, alpha,
                        a1, a2, flags, iters, units);
     return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
+static ptqtp_status quantize_check_args(const uint16_t *W, int64_t N, int64_t K, int32_t group, int32_t max_iters, double eps,
+                                        const int8_t *T1, const int8_t *T2, const uint16_t *a1, const uint16_t *a2)
+{
+    if (!W || !T1 || !T2 || !a1 || !a2) return PTQTP_ERR_NULL;
+    if (group != kGroup) return PTQTP_ERR_GROUP;
+    if (!quantize_shape_ok(N, K, group) || max_iters < 0 || max_iters > 10000 || !(eps >= 0.0))
+        return PTQTP_ERR_SHAPE;
+    if (!aligned(W, 16) || !aligned(T1, 16) || !aligned(T2, 16) || !aligned(a1, 2) || !aligned(a2, 2))
+        return PTQTP_ERR_ALIGN;
+    return PTQTP_OK;
+}
+
+ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t group, int32_t max_iters, double eps,
+                            int8_t *T1, int8_t *T2, uint16_t *a1, uint16_t *a2, int32_t *iters, void *workspace,
+                            size_t workspace_bytes, void *stream_)
+{
+    if (!workspace) return PTQTP_ERR_NULL;
+    const ptqtp_status st = quantize_check_args(W, N, K, group, max_iters, eps, T1, T2, a1, a2);
+    if (st != PTQTP_OK) return st;
+    if (workspace_bytes < ptqtp_quantize_workspace_bytes(N, K, group)) return PTQTP_ERR_SIZE;
+    if (!aligned(workspace, 256)) return PTQTP_ERR_ALIGN;
+    return quantize_enqueue(W, N, K, group, max_iters, eps, T1, T2, a1, a2, iters, workspace, stream_);
 }
 
 }  // extern "C"
