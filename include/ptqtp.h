@@ -271,6 +271,21 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ptqtp_quantize for callers that cannot allocate device memory or pass a workspace along (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same decomposition, the same kernels and
+ * bit-identical results, with the workspace in a file-scope device array of PTQTP_QUANTIZE_STATIC_BYTES (16 MiB + 256
+ * bytes, present once on every device the library runs on until the process ends).  The call allocates and frees
+ * nothing.  Layers whose workspace would be larger -- ptqtp_quantize_workspace_bytes(N, K, group) >
+ * PTQTP_QUANTIZE_STATIC_BYTES, i.e. more than 524,288 (row, group) units, e.g. above 16384 x 4096 -- are refused with
+ * PTQTP_ERR_SIZE; PTQTP_ERR_HIP if the array's address cannot be obtained on the current device.  Every call on a
+ * device shares that device's array: calls that overlap on one device (two streams, two threads) race; calls on
+ * one stream are ordered.  Other arguments and errors as for ptqtp_quantize.
+ */
+#define PTQTP_QUANTIZE_STATIC_BYTES (16u * 1024u * 1024u + 256u)
+ptqtp_status ptqtp_quantize_static(const uint16_t *W, int64_t N, int64_t K, int32_t group, int32_t max_iters, double eps,
+                                   int8_t *T1, int8_t *T2, uint16_t *a1, uint16_t *a2, int32_t *iters, void *stream);
+
+/*
  * Which kernels ptqtp_gemm would run for a shape (host logic only, no GPU needed; for tests and sweeps).
  * route[0] = PTQTP_ROUTE_*; for PTQTP_ROUTE_TILE route[1] = workgroup tile of the (first) launch
  * (0 = 256 rows x 256 tokens, 1 = 256 x 128, 2 = 128 x 128, 3 = 128 x 64, 4 = 64 x 64), route[2] = the

@@ -78,6 +78,8 @@ def _load():
         lib.ptqtp_quantize_workspace_bytes.argtypes = [i64, i64, i32]
         lib.ptqtp_quantize.restype = i32
         lib.ptqtp_quantize.argtypes = [p, i64, i64, i32, i32, ctypes.c_double, p, p, p, p, p, p, sz, p]
+        lib.ptqtp_quantize_static.restype = i32
+        lib.ptqtp_quantize_static.argtypes = [p, i64, i64, i32, i32, ctypes.c_double, p, p, p, p, p, p]
         lib.ptqtp_tune.restype = i32
         lib.ptqtp_tune.argtypes = [ctypes.c_char_p, i32]
         lib.ptqtp_gemm_route.restype = i32
@@ -283,6 +285,22 @@ def ptqtp_quantize(W: torch.Tensor, group: int = 128, max_iters: int = 50, eps: 
     if st:
         raise PtqtpError(st, "ptqtp_quantize")
     return T1, T2, a1, a2, iters
+
+
+PTQTP_QUANTIZE_STATIC_BYTES = 16 * 1024 * 1024 + 256
+
+
+def ptqtp_quantize_static(W: torch.Tensor, T1, T2, a1, a2, iters, group: int = 128, max_iters: int = 50,
+                          eps: float = 1e-4) -> None:
+    """ptqtp_quantize with the workspace in the library's static device array: the caller brings every output
+    (T1, T2 int8 [N,K]; a1, a2 fp16 [N,K/group]; iters int32[1]) and nothing is allocated, here or in the library."""
+    N, K = W.shape
+    st = _load().ptqtp_quantize_static(_dev(W, torch.float16, "W"), N, K, group, int(max_iters), float(eps),
+                                       _dev(T1, torch.int8, "T1"), _dev(T2, torch.int8, "T2"),
+                                       _dev(a1, torch.float16, "a1"), _dev(a2, torch.float16, "a2"),
+                                       _dev(iters, torch.int32, "iters"), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_quantize_static")
 
 
 PTQTP_EPI_NONE, PTQTP_EPI_SWIGLU = 0, 1

@@ -21,6 +21,7 @@
 // flag and return at once, so the host never synchronises.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <mutex>
 
 #include "ptqtp.h"
 
@@ -311,6 +312,28 @@ quant_finish_kernel(const double *__restrict__ alpha, uint16_t *__restrict__ a1,
 
 inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Workspace of ptqtp_quantize_static: one array per device the library is loaded on, held until the process ends.
+// In host code the array's name is only a stand-in for the symbol; the device address comes from
+// hipGetSymbolAddress, once per device, and is the only thing host code hands to kernels.
+__device__ __align__(256) unsigned char scratch[PTQTP_QUANTIZE_STATIC_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (nullptr on failure)
+void *scratch_address() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -381,6 +404,19 @@ ptqtp_status ptqtp_quantize(const uint16_t *W, int64_t N, int64_t K, int32_t gro
     if (workspace_bytes < ptqtp_quantize_workspace_bytes(N, K, group)) return PTQTP_ERR_SIZE;
     if (!aligned(workspace, 256)) return PTQTP_ERR_ALIGN;
     return quantize_enqueue(W, N, K, group, max_iters, eps, T1, T2, a1, a2, iters, workspace, stream_);
+}
+
+ptqtp_status ptqtp_quantize_static(const uint16_t *W, int64_t N, int64_t K, int32_t group, int32_t max_iters, double eps,
+                                   int8_t *T1, int8_t *T2, uint16_t *a1, uint16_t *a2, int32_t *iters, void *stream_)
+{
+    const ptqtp_status st = quantize_check_args(W, N, K, group, max_iters, eps, T1, T2, a1, a2);
+    if (st != PTQTP_OK) return st;
+    if (ptqtp_quantize_workspace_bytes(N, K, group) > PTQTP_QUANTIZE_STATIC_BYTES) return PTQTP_ERR_SIZE;
+    void *ws = scratch_address();
+    if (!ws) return PTQTP_ERR_HIP;
+    // the array keeps the previous call's contents: quant_begin_kernel clears the flags, the first iteration (or
+    // quant_init_state_kernel) writes every scale, lambda and partial sum before anything reads them
+    return quantize_enqueue(W, N, K, group, max_iters, eps, T1, T2, a1, a2, iters, ws, stream_);
 }
 
 }  // extern "C"
