@@ -21,9 +21,13 @@
  * Conventions for every entry point
  *   - Pointers named "device" are HIP device pointers, 16-byte aligned (the packed
  *     blob and workspace 256-byte aligned); the caller owns every buffer.  The
- *     library never allocates, frees or synchronises: work is enqueued on
- *     `stream` (a hipStream_t passed as void*, NULL = default stream) and runs
- *     asynchronously.
+ *     library never allocates or frees device memory and never synchronises: work
+ *     is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and runs asynchronously.  (The plan-writing and chain calls use a few
+ *     KB of host heap for their tables while they run.)
+ *   - Threads: every entry point except ptqtp_tune may be called from several host
+ *     threads at once (the one-time kernel attribute set-up behind the first launch
+ *     of each kernel is an idempotent call guarded by an atomic flag).
  *   - Arguments are validated on the host before anything is launched; a
  *     non-zero status means nothing was enqueued and no memory was touched.
  *   - Outputs are overwritten, never accumulated into.  Results are
@@ -96,6 +100,29 @@ ptqtp_status ptqtp_pack(const int8_t *T1, const int8_t *T2,
                         int64_t M, int64_t N, int64_t K, int32_t group,
                         void *packed, size_t packed_bytes,
                         int32_t *dev_status, void *stream);
+
+/*
+ * Check that a blob is what the compute calls are about to take it for.  The compute kernels
+ * trust the caller's N and K (they never read the header on the hot path): a blob packed for
+ * another shape, or bytes that are not a blob at all, would be streamed as they are.  This call
+ * compares the blob's header -- magic, layout id, group, N, K and the tile counts derived from
+ * them (appendix memory model: what a packed layer consists of) -- with the arguments, on the
+ * device, stream-ordered, without synchronising:
+ *   packed, packed_bytes   device blob and its size; must hold ptqtp_packed_bytes(1,N,K,group)
+ *   dev_status             device int32: receives 0 if everything matches, else an OR of
+ *                          PTQTP_BLOB_BAD_* (read it after the stream has reached this point)
+ * One thread, one 48-byte read: meant to be called once per blob when it is loaded or first used.
+ * Host-side errors (nothing launched): PTQTP_ERR_NULL, _SHAPE, _GROUP, _SIZE, _ALIGN as elsewhere.
+ */
+enum {
+    PTQTP_BLOB_BAD_MAGIC  = 1,   /* not a blob of this library                        */
+    PTQTP_BLOB_BAD_LAYOUT = 2,   /* a record layout this build does not stream         */
+    PTQTP_BLOB_BAD_GROUP  = 4,   /* packed with another group size                     */
+    PTQTP_BLOB_BAD_N      = 8,   /* packed for another number of rows                  */
+    PTQTP_BLOB_BAD_K      = 16   /* packed for another number of columns               */
+};
+ptqtp_status ptqtp_check_blob(const void *packed, size_t packed_bytes, int64_t N, int64_t K, int32_t group,
+                              int32_t *dev_status, void *stream);
 
 /*
  * Inverse of ptqtp_pack (bit-exact): recovers T1, T2 (int8 [N,K]) and a1, a2
@@ -314,7 +341,8 @@ ptqtp_status ptqtp_gemm_route(int64_t M, int64_t N, int64_t K, int32_t group, in
  * 0 = default: the cheapest by a cost model of the problem size; also honoured by ptqtp_chain_run_batch
  * above PTQTP_GEMM_SMALL_MAX_M tokens where the stage allows the tile);
  * value 0 restores the built-in heuristic.  Returns PTQTP_ERR_SHAPE for an
- * unknown key or out-of-range value.  Not thread-safe.
+ * unknown key or out-of-range value.  Not thread-safe: the overrides are process-wide globals, to be set while no
+ * other thread is inside the library.
  */
 ptqtp_status ptqtp_tune(const char *key, int32_t value);
 

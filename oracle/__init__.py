@@ -47,41 +47,64 @@ def build(force: bool = False) -> str:
 
 def _bind(lib):
     """Declare the C signatures on a loaded library (the built one, or a deliberately broken copy in the mutation tests)."""
-    if True:
-        p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
-        lib.ptqtp_oracle_half_to_double.restype = ctypes.c_double
-        lib.ptqtp_oracle_half_to_double.argtypes = [ctypes.c_uint16]
-        lib.ptqtp_oracle_forward_f64x.restype = i32
-        lib.ptqtp_oracle_forward_f64x.argtypes = [p, p, p, p, p, i64, i64, i64, i64, p, p, i32]
-        lib.ptqtp_oracle_forward.restype = i32
-        lib.ptqtp_oracle_forward.argtypes = [p, p, p, p, p, p, i64, i64, i64, i64, p, p, i32]
-        lib.ptqtp_oracle_pack_canonical.restype = i32
-        lib.ptqtp_oracle_pack_canonical.argtypes = [p, i64, i64, p]
-        lib.ptqtp_oracle_unpack_canonical.restype = i32
-        lib.ptqtp_oracle_unpack_canonical.argtypes = [p, i64, i64, p]
-        lib.ptqtp_oracle_model_bits.restype = i64
-        lib.ptqtp_oracle_model_bits.argtypes = [i64, i64, i64]
-        lib.ptqtp_oracle_quantize.restype = i32
-        lib.ptqtp_oracle_quantize.argtypes = [p, i64, i64, i64, i32, ctypes.c_double, p, p, p, p, p, p, p, p]
-        lib.ptqtp_oracle_double_to_half_bits.restype = ctypes.c_uint16
-        lib.ptqtp_oracle_double_to_half_bits.argtypes = [ctypes.c_double]
-        lib.ptqtp_oracle_silu.restype = ctypes.c_double
-        lib.ptqtp_oracle_silu.argtypes = [ctypes.c_double]
-        lib.ptqtp_oracle_swiglu.restype = i32
-        lib.ptqtp_oracle_swiglu.argtypes = [p, i64, i64, p]
-        lib.ptqtp_oracle_residual_add.restype = i32
-        lib.ptqtp_oracle_residual_add.argtypes = [p, p, i64, p]
-        lib.ptqtp_oracle_round_half.restype = ctypes.c_double
-        lib.ptqtp_oracle_round_half.argtypes = [ctypes.c_double]
-        lib.ptqtp_oracle_round_half_array.restype = None
-        lib.ptqtp_oracle_round_half_array.argtypes = [p, i64, p]
+    p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    lib.ptqtp_oracle_half_to_double.restype = ctypes.c_double
+    lib.ptqtp_oracle_half_to_double.argtypes = [ctypes.c_uint16]
+    lib.ptqtp_oracle_forward_f64x.restype = i32
+    lib.ptqtp_oracle_forward_f64x.argtypes = [p, p, p, p, p, i64, i64, i64, i64, p, p, i32]
+    lib.ptqtp_oracle_forward.restype = i32
+    lib.ptqtp_oracle_forward.argtypes = [p, p, p, p, p, p, i64, i64, i64, i64, p, p, i32]
+    lib.ptqtp_oracle_pack_canonical.restype = i32
+    lib.ptqtp_oracle_pack_canonical.argtypes = [p, i64, i64, p]
+    lib.ptqtp_oracle_unpack_canonical.restype = i32
+    lib.ptqtp_oracle_unpack_canonical.argtypes = [p, i64, i64, p]
+    lib.ptqtp_oracle_model_bits.restype = i64
+    lib.ptqtp_oracle_model_bits.argtypes = [i64, i64, i64]
+    lib.ptqtp_oracle_quantize.restype = i32
+    lib.ptqtp_oracle_quantize.argtypes = [p, i64, i64, i64, i32, ctypes.c_double, p, p, p, p, p, p, p, p]
+    lib.ptqtp_oracle_double_to_half_bits.restype = ctypes.c_uint16
+    lib.ptqtp_oracle_double_to_half_bits.argtypes = [ctypes.c_double]
+    lib.ptqtp_oracle_silu.restype = ctypes.c_double
+    lib.ptqtp_oracle_silu.argtypes = [ctypes.c_double]
+    lib.ptqtp_oracle_swiglu.restype = i32
+    lib.ptqtp_oracle_swiglu.argtypes = [p, i64, i64, p]
+    lib.ptqtp_oracle_residual_add.restype = i32
+    lib.ptqtp_oracle_residual_add.argtypes = [p, p, i64, p]
+    lib.ptqtp_oracle_round_half.restype = ctypes.c_double
+    lib.ptqtp_oracle_round_half.argtypes = [ctypes.c_double]
+    lib.ptqtp_oracle_round_half_array.restype = None
+    lib.ptqtp_oracle_round_half_array.argtypes = [p, i64, p]
     return lib
+
+
+_LIB_SAN = os.path.join(_HERE, "libptqtp_oracle_san.so")
+SANITIZED_ENV = "PTQTP_ORACLE_SANITIZED"      # set to 1: load the AddressSanitizer/UBSan build (see build_sanitized)
+
+
+def build_sanitized() -> str:
+    """The same sources with -fsanitize=address,undefined (host code only, gcc): memory errors and undefined
+    behaviour in the oracle abort the process that loads it.  The process must have the sanitizer runtime
+    preloaded (sanitizer_preload()); tests/test_oracle_sanitized.py runs the pin tests that way."""
+    tmp = _LIB_SAN + f".tmp{os.getpid()}"
+    subprocess.check_call(["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+                           "-o", tmp, _SRC, _SRC_Q, _SRC_B, "-lm"])
+    os.replace(tmp, _LIB_SAN)
+    return _LIB_SAN
+
+
+def sanitizer_preload() -> str:
+    """Path of gcc's AddressSanitizer runtime, for LD_PRELOAD of a process that loads the sanitized build."""
+    return subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
 
 
 def _load():
     global _lib
     if _lib is None:
-        _lib = _bind(ctypes.CDLL(build()))
+        if os.environ.get(SANITIZED_ENV) == "1":
+            _lib = _bind(ctypes.CDLL(_LIB_SAN if os.path.exists(_LIB_SAN) else build_sanitized()))
+        else:
+            _lib = _bind(ctypes.CDLL(build()))
     return _lib
 
 

@@ -7,6 +7,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import weakref
 
 import torch
 
@@ -48,6 +49,8 @@ def _load():
         lib.ptqtp_workspace_bytes.argtypes = [i64, i64, i64, i32]
         lib.ptqtp_pack.restype = i32
         lib.ptqtp_pack.argtypes = [p, p, p, p, i64, i64, i64, i32, p, sz, p, p]
+        lib.ptqtp_check_blob.restype = i32
+        lib.ptqtp_check_blob.argtypes = [p, sz, i64, i64, i32, p, p]
         lib.ptqtp_unpack.restype = i32
         lib.ptqtp_unpack.argtypes = [p, i64, i64, i64, i32, p, p, p, p, p]
         lib.ptqtp_gemv.restype = i32
@@ -153,6 +156,7 @@ def ptqtp_pack(T1, T2, a1, a2, M: int = 1, group: int = 128, check: bool = True)
         raise PtqtpError(st, "ptqtp_pack")
     if check and int(status.item()) != 0:
         raise ValueError("ptqtp_pack: a plane holds a value outside {-1, 0, +1}")
+    _mark_checked(packed, N, K, group)          # written by the library for this very shape
     return packed
 
 
@@ -170,13 +174,53 @@ def ptqtp_unpack(packed: torch.Tensor, N: int, K: int, M: int = 1, group: int = 
     return T1, T2, a1, a2
 
 
+PTQTP_BLOB_BAD_MAGIC, PTQTP_BLOB_BAD_LAYOUT, PTQTP_BLOB_BAD_GROUP, PTQTP_BLOB_BAD_N, PTQTP_BLOB_BAD_K = 1, 2, 4, 8, 16
+_checked = {}      # id(blob tensor) -> (weak reference to it, set of (N, K, group, version) already found good)
+
+
+def _good_shapes(packed: torch.Tensor):
+    entry = _checked.get(id(packed))
+    return entry[1] if entry is not None and entry[0]() is packed else None
+
+
+def ptqtp_check_blob(packed: torch.Tensor, N: int, K: int, group: int = 128) -> int:
+    """Header of `packed` against (N, K, group) on the device; returns the PTQTP_BLOB_BAD_* bits (0 = good).
+    Synchronises to read the status word."""
+    status = torch.empty(1, dtype=torch.int32, device=packed.device)
+    st = _load().ptqtp_check_blob(_dev(packed, torch.uint8, "packed"), packed.numel(), int(N), int(K), int(group),
+                                  status.data_ptr(), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_check_blob")
+    return int(status.item())
+
+
+def _mark_checked(packed: torch.Tensor, N: int, K: int, group: int) -> None:
+    shapes = _good_shapes(packed)
+    if shapes is None:
+        key, shapes = id(packed), set()
+        _checked[key] = (weakref.ref(packed, lambda _ref, key=key: _checked.pop(key, None)), shapes)
+    shapes.add((int(N), int(K), int(group), packed._version))
+
+
 def _check_blob(packed: torch.Tensor, N: int, K: int, group: int, where: str) -> None:
-    """The kernels trust N and K: a blob shorter than those need would be read past its end."""
+    """The kernels trust N and K: a blob shorter than those need would be read past its end, and one packed for
+    another shape would be streamed as it is.  Size on the host at every call; the header on the device once per
+    (blob, shape) -- not while the stream is being captured, where nothing can be read back."""
     need = ptqtp_packed_bytes(1, N, K, group)
     if need == 0:
         raise PtqtpError(2 if group == 128 else 3, where)
     if packed.numel() < need:
         raise PtqtpError(4, where)
+    key = (int(N), int(K), int(group), packed._version)
+    if not packed.is_cuda:                      # refused with a TypeError where its pointer is taken
+        return
+    if key in (_good_shapes(packed) or ()) or torch.cuda.is_current_stream_capturing():
+        return
+    bad = ptqtp_check_blob(packed, N, K, group)
+    if bad:
+        names = [n for b, n in ((1, "magic"), (2, "layout id"), (4, "group"), (8, "N"), (16, "K")) if bad & b]
+        raise ValueError(f"{where}: the blob's header does not match N={N}, K={K}, group={group} ({', '.join(names)} differ)")
+    _mark_checked(packed, N, K, group)
 
 
 def _forward(fn, where, packed, x, N, K, M, group, y_dtype, out):

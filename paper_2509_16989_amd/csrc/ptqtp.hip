@@ -32,6 +32,7 @@
 #include <stdint.h>
 #include <string.h>
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 #include <vector>
 
@@ -78,6 +79,20 @@ inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintp
 // pack / unpack
 // ------------------------------------------------------------------------------------------
 __global__ void clear_status_kernel(int32_t *st) { *st = 0; }
+
+// Header of a blob against the shape the caller is about to use it with: a bit per field that differs.
+__global__ void check_blob_kernel(const uint8_t *__restrict__ blob, int64_t N, int64_t K, int64_t RT, int64_t KS,
+                                  int32_t *__restrict__ dev_status)
+{
+    const BlobHeader h = *reinterpret_cast<const BlobHeader *>(blob);
+    int32_t bad = 0;
+    if (h.magic != kMagic) bad |= PTQTP_BLOB_BAD_MAGIC;
+    if (h.layout != kLayoutId) bad |= PTQTP_BLOB_BAD_LAYOUT;
+    if (h.group != 128) bad |= PTQTP_BLOB_BAD_GROUP;
+    if (h.N != N || h.RT != RT) bad |= PTQTP_BLOB_BAD_N;
+    if (h.K != K || h.KS != KS) bad |= PTQTP_BLOB_BAD_K;
+    *dev_status = bad;
+}
 
 // Four trits held as int8 bytes of x -> their 2-bit codes at nibble j of a 16-bit result, the nonzero bit at nibble
 // bit 1 - par and the sign at 3 - par (the layout of one parity of a plane word).  For a valid byte (0x00, 0x01, 0xff)
@@ -631,17 +646,17 @@ constexpr int kTileChunk = 1040;                    // 1 KiB chunk of four token
 // becomes lgkmcnt(0) and operand reads issued ahead of their use buy nothing.  Hidden from that pass, the loads are
 // waited for by hand (s_waitcnt vmcnt(0) before the barrier that publishes the buffer); loads the pass does not know
 // of can only make its own vmcnt waits stricter, never weaker, because the counter retires in issue order.
-// M0 (the LDS base of the load) is a register the compiler reserves for the few instructions that read it implicitly and
-// sets right before each of them; the kernels here contain none of those (no builtin LDS-direct loads, no indexed
-// register access, no messages), so writing it in the asm statement disturbs nothing -- the diagnostic about a reserved
-// register in the clobber list is silenced on that ground.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
+// M0 (the LDS base of the load) is a register the compiler reserves for the instructions that read it implicitly; the
+// statement saves it in a scalar temporary and puts it back after the load has been issued, so nothing is assumed
+// about what else the compiler keeps there.  One wait state separates the scalar write of M0 from the load that
+// reads it.
 __device__ __forceinline__ void lds_direct_load16(const void *gptr, const char *lds_base)
 {
     const uint32_t lds_off = static_cast<uint32_t>(reinterpret_cast<size_t>(
         (const __attribute__((address_space(3))) char *)lds_base));
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory", "m0");
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "v"(gptr), "s"(lds_off) : "memory");
 }
 #pragma clang diagnostic pop
 
@@ -1012,12 +1027,12 @@ hipError_t launch_gemm_tile3(const uint8_t *records, const uint16_t *x, void *y,
     const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
     if (grid <= 0 || grid > kMaxGrid) return hipErrorInvalidValue;
     const size_t lds = 2 * static_cast<size_t>(kTile3BufBytes);
-    static bool configured = false;                  // raise the dynamic LDS limit once per process
-    if (!configured) {
+    static std::atomic<bool> configured{false};                  // raise the dynamic LDS limit once per process
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile3_kernel<FUSE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((gemm_tile3_kernel<FUSE>), dim3(static_cast<unsigned>(grid)), dim3(512), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
@@ -1038,12 +1053,12 @@ hipError_t launch_gemm_tile(const uint8_t *records, const uint16_t *x, void *y, 
     const int64_t grid = static_cast<int64_t>((NB - nb0 + 7) / 8) * 8 * MB;
     if (grid <= 0 || grid > kMaxGrid) return hipErrorInvalidValue;
     const size_t lds = 2 * static_cast<size_t>(TM / 4) * kTileChunk;
-    static bool configured = false;                  // raise the dynamic LDS limit once per process
-    if (!configured) {
+    static std::atomic<bool> configured{false};                  // raise the dynamic LDS limit once per process
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<MTW, FUSE, RTW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((gemm_tile_kernel<MTW, FUSE, RTW>), dim3(static_cast<unsigned>(grid)), dim3(256), lds, stream, records, x,
                        y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
@@ -1131,12 +1146,12 @@ hipError_t launch_gemm_items_impl(const PlanHeader *plan, const uint8_t *records
 {
     size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
     if (lds < static_cast<size_t>(W) * kSlotBytes) lds = static_cast<size_t>(W) * kSlotBytes;
-    static bool configured = false;                  // the slots of 8 waves exceed the default 64 KB limit
-    if (!configured) {
+    static std::atomic<bool> configured{false};                  // the slots of 8 waves exceed the default 64 KB limit
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_items_kernel<MT, R, S, PLAN, ML>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 8 * kSlotBytes);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((gemm_items_kernel<MT, R, S, PLAN, ML>), dim3(static_cast<unsigned>(grid)), dim3(W * 64), lds,
                        stream, plan, records, x, y, M, N, K, RT, KS, y_f16, residual, gated);
@@ -1401,12 +1416,12 @@ hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStr
 {
     static_assert(NW * RTW <= kPlanPad, "a workgroup's row tiles belong to one linear");
     const size_t lds = 2 * static_cast<size_t>((MT + 1) / 2) * 16 * kRowsChunk<MT>;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW, FOLD, NW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((gemm_rows_kernel<MT, RTW, FOLD, NW>), dim3(static_cast<unsigned>((items + NW * RTW - 1) / (NW * RTW))),
                        dim3(64 * NW), lds, stream, plan, M);
@@ -1599,6 +1614,19 @@ size_t ptqtp_packed_bytes(int64_t M, int64_t N, int64_t K, int32_t group) {
 }
 
 size_t ptqtp_workspace_bytes(int64_t, int64_t, int64_t, int32_t) { return 0; }
+
+ptqtp_status ptqtp_check_blob(const void *packed, size_t packed_bytes, int64_t N, int64_t K, int32_t group,
+                              int32_t *dev_status, void *stream_) {
+    if (!packed || !dev_status) return PTQTP_ERR_NULL;
+    Shape s;
+    ptqtp_status st;
+    if (!make_shape(1, N, K, group, &s, &st)) return st;
+    if (packed_bytes < ptqtp_packed_bytes(1, N, K, group)) return PTQTP_ERR_SIZE;
+    if (!aligned(packed, 256) || !aligned(dev_status, 4)) return PTQTP_ERR_ALIGN;
+    hipLaunchKernelGGL(check_blob_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream_),
+                       static_cast<const uint8_t *>(packed), s.N, s.K, s.RT, s.KS, dev_status);
+    return hipGetLastError() == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
 
 ptqtp_status ptqtp_pack(const int8_t *T1, const int8_t *T2, const uint16_t *a1, const uint16_t *a2,
                         int64_t M, int64_t N, int64_t K, int32_t group, void *packed, size_t packed_bytes,

@@ -31,7 +31,8 @@ def test_header_symbols_exported(lib):
             "ptqtp_workspace_bytes", "ptqtp_status_string", "ptqtp_version", "ptqtp_tune", "ptqtp_gemm",
             "ptqtp_gemv_batch", "ptqtp_gemv_batch_plan", "ptqtp_batch_items", "ptqtp_batch_plan_bytes",
             "ptqtp_quantize", "ptqtp_quantize_workspace_bytes", "ptqtp_gemm_batch", "ptqtp_chain_plan_bytes",
-            "ptqtp_chain_plan", "ptqtp_chain_run", "ptqtp_chain_run_batch", "ptqtp_gemm_route"} <= set(names)
+            "ptqtp_chain_plan", "ptqtp_chain_run", "ptqtp_chain_run_batch", "ptqtp_gemm_route", "ptqtp_check_blob",
+            "ptqtp_quantize_static"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in ptqtp.h but not exported"
 
@@ -145,6 +146,27 @@ def test_quantize_validation(lib):
     assert lib.ptqtp_quantize(*args(eps=float("nan"))) == 2
     assert lib.ptqtp_quantize(*args(wsb=100)) == 4
     assert lib.ptqtp_quantize(*args(ws=ctypes.c_void_p(0x10010))) == 6
+
+
+def test_check_blob_and_static_quantizer_validation(lib):
+    fake, status = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000)
+    need = lib.ptqtp_packed_bytes(1, 64, 256, 128)
+    assert lib.ptqtp_check_blob(None, need, 64, 256, 128, status, None) == 1
+    assert lib.ptqtp_check_blob(fake, need, 64, 256, 128, None, None) == 1
+    assert lib.ptqtp_check_blob(fake, need, 64, 200, 128, status, None) == 2
+    assert lib.ptqtp_check_blob(fake, need, 64, 256, 64, status, None) == 3
+    assert lib.ptqtp_check_blob(fake, need - 1, 64, 256, 128, status, None) == 4
+    assert lib.ptqtp_check_blob(ctypes.c_void_p(0x10080), need, 64, 256, 128, status, None) == 6
+    assert lib.ptqtp_check_blob(fake, need, 64, 256, 128, ctypes.c_void_p(0x20002), None) == 6
+    # the static-workspace quantizer refuses on the host what its array cannot hold, and bad arguments as ptqtp_quantize does
+    args = lambda **k: [k.get("W", fake), k.get("N", 64), k.get("K", 256), k.get("group", 128), k.get("iters", 50),
+                        ctypes.c_double(k.get("eps", 1e-4)), fake, fake, fake, fake, None, None]
+    assert lib.ptqtp_quantize_static(*args(W=None)) == 1
+    assert lib.ptqtp_quantize_static(*args(group=64)) == 3
+    assert lib.ptqtp_quantize_static(*args(K=200)) == 2
+    assert lib.ptqtp_quantize_static(*args(iters=-1)) == 2
+    assert lib.ptqtp_quantize_static(*args(N=16385, K=4096)) == 4
+    assert lib.ptqtp_quantize_static(*args(N=1 << 20, K=1 << 17)) == 4
 
 
 def test_size_limits(lib):

@@ -646,6 +646,40 @@ def test_gemm_small_fp16_output_and_guard(ptq):
     assert (buf[:64] == 7).all() and (buf[64 + M * N:] == 7).all()
 
 
+def test_check_blob_flags_what_does_not_match(ptq):
+    # the compute kernels trust N and K; the header check is what stands between a wrong blob and silent garbage
+    N, K = 64, 512
+    lin = workloads.make_linear(N, K, 64)
+    packed = pack(ptq, lin)
+    assert ptq.ptqtp_check_blob(packed, N, K) == 0
+    # another shape with the very same byte count (8 records either way), and a smaller one that fits inside
+    assert ptq.ptqtp_packed_bytes(1, 128, 256) == packed.numel()
+    assert ptq.ptqtp_check_blob(packed, 128, 256) == ptq.PTQTP_BLOB_BAD_N | ptq.PTQTP_BLOB_BAD_K
+    assert ptq.ptqtp_check_blob(packed, 48, K) == ptq.PTQTP_BLOB_BAD_N
+    assert ptq.ptqtp_check_blob(packed, N, 256) == ptq.PTQTP_BLOB_BAD_K
+    x = dev(workloads.make_x(1, 256, 64)).reshape(-1)
+    with pytest.raises(ValueError, match="header does not match"):
+        ptq.ptqtp_gemv(packed, x, 128, 256)
+    with pytest.raises(ValueError, match="header does not match"):
+        ptq.ptqtp_unpack(packed, 128, 256)
+    # corrupted header fields: magic (bytes 0..7), layout id (8..11), group (12..15)
+    for offset, bit in ((0, ptq.PTQTP_BLOB_BAD_MAGIC), (5, ptq.PTQTP_BLOB_BAD_MAGIC), (8, ptq.PTQTP_BLOB_BAD_LAYOUT),
+                        (12, ptq.PTQTP_BLOB_BAD_GROUP)):
+        bad = packed.clone()
+        bad[offset] ^= 0x40
+        assert ptq.ptqtp_check_blob(bad, N, K) == bit
+        with pytest.raises(ValueError, match="header does not match"):
+            ptq.ptqtp_gemv(bad, dev(workloads.make_x(1, K, 64)).reshape(-1), N, K)
+    # a blob that was good and is then written to is looked at again
+    xk = dev(workloads.make_x(1, K, 64)).reshape(-1)
+    ptq.ptqtp_gemv(packed, xk, N, K)
+    packed[0] ^= 0xff
+    with pytest.raises(ValueError, match="magic"):
+        ptq.ptqtp_gemv(packed, xk, N, K)
+    packed[0] ^= 0xff
+    check(ptq.ptqtp_gemv(packed, xk, N, K), lin, workloads.make_x(1, K, 64))
+
+
 # ---------------------------------------------------------------- full-size layers, sampled rows
 def _sampled_rows_check(ptq, lin, x, y, rows):
     sub_ref, B = oracle.forward(lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows], x, threads=8)
