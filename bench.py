@@ -142,6 +142,17 @@ def time_steps(torch, step, steps, warmup, stream, stats=None):
     return max(ev0.elapsed_time(ev1), wall * 1e3) / steps
 
 
+def preheat(step, stream, ms=150.0):
+    """Run `step` untimed for `ms` milliseconds: every figure is taken at the clocks of a GPU that is serving, not of
+    one that has just waited for the host to set up the next case (the first steps after an idle spell run 5-10 %
+    slower and would sit in the mean)."""
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(10):
+            step()
+        stream.synchronize()
+
+
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix rate
 RIDGE_TOKENS = 41               # 7.5 * M operations per byte of the packed stream: the two roofs cross near 41 tokens
 
@@ -186,7 +197,8 @@ def per_config_timing(ptq, torch, workloads, blobs, jobs, dims, stream, note):
             plan = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xm, ym, dims)])
             stream.synchronize()
             st = {}
-            ms = time_steps(torch, lambda: ptq.ptqtp_gemm_batch(plan, M), 30, 10, stream, stats=st)
+            preheat(lambda: ptq.ptqtp_gemm_batch(plan, M), stream)
+            ms = time_steps(torch, lambda: ptq.ptqtp_gemm_batch(plan, M), 50, 10, stream, stats=st)
             ent = roof_entry(ms * 1e3, dims, M)
             ent.update(median_us=st["median_us"], min_us=st["min_us"])
             res[f"8b_stack_one_launch_M{M}"] = ent
@@ -292,6 +304,7 @@ def main() -> int:
             extra["us_per_stack_pass_other_launch_modes"] = others
             if args.mode != "chain":
                 cst = {}
+                preheat(chain.replay, stream)
                 chain_us = time_steps(torch, chain.replay, 100, 20, stream, stats=cst) * 1e3
             else:
                 cst, chain_us = stats, ms_per_step * 1e3
@@ -379,7 +392,7 @@ def recorded_traffic(mode: str, layers: int) -> dict:
                               f"source hash {src_hash}; not measured by this run"}
 
 
-def _graph_time(torch, stream, run, launches, reps=10):
+def _graph_time(torch, stream, run, launches, reps=10, heat_ms=30.0):
     """us per launch of `run` (which enqueues `launches` library calls), replayed from a hipGraph."""
     run()
     stream.synchronize()
@@ -388,6 +401,7 @@ def _graph_time(torch, stream, run, launches, reps=10):
         run()
     g.replay()
     stream.synchronize()
+    preheat(g.replay, stream, ms=heat_ms)
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     e0.record(stream)
