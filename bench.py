@@ -234,6 +234,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true",
                     help="time only the step of --mode (for runs under a profiler)")
+    ap.add_argument("--no-chain", action="store_true",
+                    help="leave the dependent decode chain (and its hipGraph) out: for counter runs, where rocprofv3's "
+                         "counter collection has crashed on the replay of that graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run 5 plain 1 GiB device copies (known HBM traffic) and exit: the reference that "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -278,7 +281,7 @@ def main() -> int:
     extra = {}
     chain = None
     with torch.cuda.stream(stream):
-        if args.mode == "chain" or not args.no_per_config:
+        if args.mode == "chain" or not (args.no_per_config or args.no_chain):
             chain = DecodeChain(ptq, torch, blobs, jobs, dims, stream)
         if args.mode == "chain":
             step, launches_step, bytes_step = chain.replay, chain.launches, chain.nbytes
@@ -302,26 +305,27 @@ def main() -> int:
                     st, _ = make_step(ptq, torch, mode, blobs, xs, ys, dims, stream)
                     others[mode] = round(time_steps(torch, st, max(3, args.steps // 5), 2, stream) * 1e3, 2)
             extra["us_per_stack_pass_other_launch_modes"] = others
-            if args.mode != "chain":
+            if args.mode != "chain" and chain is not None:
                 cst = {}
                 preheat(chain.replay, stream)
                 chain_us = time_steps(torch, chain.replay, 100, 20, stream, stats=cst) * 1e3
             else:
                 cst, chain_us = stats, ms_per_step * 1e3
             note("dependent chain done")
-            extra["us_per_decode_step"] = round(chain_us, 2)
-            extra["decode_step"] = {
-                "what": "dependent decode step: per layer qkv -> o (+residual) -> gate|up (silu(gate)*up) -> down "
-                        "(+residual), fp16 activations, ptqtp_chain_run replayed from one hipGraph",
-                "us": round(chain_us, 2), "median_us": cst["median_us"], "min_us": cst["min_us"],
-                "launches": chain.launches, "bytes_per_step": chain.nbytes,
-                "GBps": round(chain.nbytes / chain_us / 1e3, 1), "bound": "hbm",
-                "frac": round(chain.nbytes / chain_us / 1e3 / HBM_PEAK_GBS, 4),
-                "agrees_with_unfused_calls": chain.self_check()}
+            if chain is not None:
+                extra["us_per_decode_step"] = round(chain_us, 2)
+                extra["decode_step"] = {
+                    "what": "dependent decode step: per layer qkv -> o (+residual) -> gate|up (silu(gate)*up) -> down "
+                            "(+residual), fp16 activations, ptqtp_chain_run replayed from one hipGraph",
+                    "us": round(chain_us, 2), "median_us": cst["median_us"], "min_us": cst["min_us"],
+                    "launches": chain.launches, "bytes_per_step": chain.nbytes,
+                    "GBps": round(chain.nbytes / chain_us / 1e3, 1), "bound": "hbm",
+                    "frac": round(chain.nbytes / chain_us / 1e3 / HBM_PEAK_GBS, 4),
+                    "agrees_with_unfused_calls": chain.self_check()}
             extra["per_config"] = per_config_timing(ptq, torch, workloads, blobs, jobs, dims, stream, note)
         if args.per_shape:
             extra["per_shape"] = per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, args.no_cpu_baseline,
-                                                  quick=args.steps < 50, chain=chain)
+                                                  quick=args.steps < 50, chain=chain, no_chain=args.no_chain)
 
     gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
     launch_us = ms_per_step * 1e3 / launches_step
@@ -412,7 +416,7 @@ def _graph_time(torch, stream, run, launches, reps=10, heat_ms=30.0):
     return e0.elapsed_time(e1) * 1e3 / (reps * launches)
 
 
-def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False, quick=False, chain=None):
+def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False, quick=False, chain=None, no_chain=False):
     """The workloads beside the headline, one linear per launch:
     each 8B shape at M = 1, 4, 16, 64, cold (walking the 32 layer copies) -- and M = 1 hot, and short prompts
     (M = 128, 512) on the small MFMA tiles;
@@ -491,10 +495,11 @@ def per_shape_timing(ptq, torch, blobs, xs, ys, jobs, dims, stream, no_cpu=False
         # config 3 with the activations really depending on each other: per layer qkv -> o (+residual) ->
         # gate|up (silu(gate)*up) -> down (+residual), fp16 activations, one launch per stage (128 launches)
         # replayed from a hipGraph.  Attention itself is not part of the path: o reads the q part of qkv's output.
-        if chain is None:
-            chain = DecodeChain(ptq, torch, blobs, jobs, dims, stream)
-        res["dependent_chain"] = chain.extras(quick)
-        note("dependent chain done")
+        if not no_chain:
+            if chain is None:
+                chain = DecodeChain(ptq, torch, blobs, jobs, dims, stream)
+            res["dependent_chain"] = chain.extras(quick)
+            note("dependent chain done")
         # the step before the path: PTQTP decomposition of Gaussian fp16 weights (paper settings: T_max 50, eps 1e-4)
         res["quantize"] = {}
         for name in ("q", "gate"):
