@@ -202,6 +202,20 @@ def per_config_timing(ptq, torch, workloads, blobs, jobs, dims, stream, note):
             ent = roof_entry(ms * 1e3, dims, M)
             ent.update(median_us=st["median_us"], min_us=st["min_us"])
             res[f"8b_stack_one_launch_M{M}"] = ent
+            if M == 64:
+                # the same launch with the planes summed in fp16 before the matrix pipe (ptqtp_gemm_batch_fused)
+                st = {}
+                preheat(lambda: ptq.ptqtp_gemm_batch_fused(plan, M), stream)
+                ms = time_steps(torch, lambda: ptq.ptqtp_gemm_batch_fused(plan, M), 50, 10, stream, stats=st)
+                us = ms * 1e3
+                nbytes = sum(algorithmic_bytes(n, k, M) for n, k in dims)
+                flops = sum(4.0 * M * n * k for n, k in dims)
+                # half the matrix operations are executed: the HBM stream is the roof that binds (465 us against 357)
+                res[f"8b_stack_one_launch_M{M}_fused_planes"] = {
+                    "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                    "TFLOPs_counted_as_two_planes": round(flops / us / 1e6, 1), "bound": "hbm",
+                    "frac": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                    "median_us": st["median_us"], "min_us": st["min_us"], "arithmetic": "PTQTP_FUSED_PLANES"}
             del xm, ym, plan
             note(f"stack at M={M} done")
         for name in ("gate", "down"):

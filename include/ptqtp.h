@@ -219,6 +219,16 @@ ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream);
 ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *stream);
 
 /*
+ * ptqtp_gemm_batch with the arithmetic of PTQTP_FUSED_PLANES where that pays: from 33 tokens on, each weight is
+ * rebuilt before the matrix pipe, w16 = fp16(alpha1*t1 + alpha2*t2) (one rounding, both products exact in fp16:
+ * the "dequantization" forward of Sec. "Inference Efficiency"), and one MFMA pass runs over w16 instead of one per
+ * plane; the result is the exact layer of the rounded weights, |y - y_unfused| <= 2^-11 * B as for ptqtp_gemm.
+ * Up to 32 tokens, where the matrix pipe is not what binds, the call is ptqtp_gemm_batch bit for bit.
+ * Arguments and errors as in ptqtp_gemm_batch.
+ */
+ptqtp_status ptqtp_gemm_batch_fused(const void *plan, int64_t items, int64_t M, void *stream);
+
+/*
  * Decode chain: the dependent linears of a decoder block (and of a whole stack of blocks) at
  * batch 1, with the steps either side of them fused into the producing kernel.  The paper
  * replaces every linear projection of LLaMA-family blocks (Sec. "Experiments", setup) and

@@ -77,6 +77,8 @@ def _load():
         lib.ptqtp_gemv_batch.argtypes = [p, i64, p]
         lib.ptqtp_gemm_batch.restype = i32
         lib.ptqtp_gemm_batch.argtypes = [p, i64, i64, p]
+        lib.ptqtp_gemm_batch_fused.restype = i32
+        lib.ptqtp_gemm_batch_fused.argtypes = [p, i64, i64, p]
         lib.ptqtp_quantize_workspace_bytes.restype = sz
         lib.ptqtp_quantize_workspace_bytes.argtypes = [i64, i64, i32]
         lib.ptqtp_quantize.restype = i32
@@ -302,6 +304,15 @@ def ptqtp_gemm_batch(plan: BatchPlan, M: int) -> None:
     st = _load().ptqtp_gemm_batch(plan.plan.data_ptr(), plan.items, int(M), _stream())
     if st:
         raise PtqtpError(st, "ptqtp_gemm_batch")
+
+
+def ptqtp_gemm_batch_fused(plan: BatchPlan, M: int) -> None:
+    """ptqtp_gemm_batch with the planes summed in fp16 before the matrix pipe from 33 tokens on."""
+    if M > plan.tokens:
+        raise PtqtpError(2, "ptqtp_gemm_batch_fused")
+    st = _load().ptqtp_gemm_batch_fused(plan.plan.data_ptr(), plan.items, int(M), _stream())
+    if st:
+        raise PtqtpError(st, "ptqtp_gemm_batch_fused")
 
 
 def ptqtp_gemv_batch(plan: BatchPlan) -> None:

@@ -1235,7 +1235,7 @@ __device__ __forceinline__ constexpr int rows_operand_offset(int mt, int f) {
     return (mt >> 1) * (16 * kRowsChunk<MT>) + (mt & 1) * 512 + f * 64;
 }
 
-template <int MT, int RTW, bool FOLD, int NW = 4>
+template <int MT, int RTW, bool FOLD, int NW = 4, bool FUSE = false>
 __global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu((!FOLD && MT * RTW >= 8) ? 1 : 2)))
 gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
 {
@@ -1296,17 +1296,19 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
                         a[(f + 1) & 1][mt] = __builtin_bit_cast(
                             half8, *reinterpret_cast<const uintx4 *>(xb + rows_operand_offset<MT>(mt, f + 1)));
                 }
-                half8 b[2][RTW];
+                constexpr int NPL = FUSE ? 1 : 2;
+                half8 b[NPL][RTW];
 #pragma unroll
                 for (int t = 0; t < RTW; ++t) {
                     const _Float16 a1 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(g2 ? (r[t].sc.x >> 16) : (r[t].sc.x & 0xffffu)));
                     const _Float16 a2 = __builtin_bit_cast(_Float16, static_cast<uint16_t>(g2 ? (r[t].sc.y >> 16) : (r[t].sc.y & 0xffffu)));
-                    b[0][t] = decode8(r[t].p1[wi], par) * half8{a1, a1, a1, a1, a1, a1, a1, a1};
-                    b[1][t] = decode8(r[t].p2[wi], par) * half8{a2, a2, a2, a2, a2, a2, a2, a2};
+                    const half8 w1 = decode8(r[t].p1[wi], par) * half8{a1, a1, a1, a1, a1, a1, a1, a1};
+                    const half8 w2 = decode8(r[t].p2[wi], par) * half8{a2, a2, a2, a2, a2, a2, a2, a2};
+                    if constexpr (FUSE) { b[0][t] = w1 + w2; } else { b[0][t] = w1; b[NPL - 1][t] = w2; }
                 }
                 // consecutive MFMAs write different accumulators
 #pragma unroll
-                for (int pl = 0; pl < 2; ++pl)
+                for (int pl = 0; pl < NPL; ++pl)
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -1414,19 +1416,19 @@ gemm_rows_kernel(const PlanHeader *__restrict__ plan, int M)
     }
 }
 
-template <int MT, int RTW, bool FOLD, int NW = 4>
+template <int MT, int RTW, bool FOLD, int NW = 4, bool FUSE = false>
 hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStream_t stream)
 {
     static_assert(NW * RTW <= kPlanPad, "a workgroup's row tiles belong to one linear");
     const size_t lds = 2 * static_cast<size_t>((MT + 1) / 2) * 16 * kRowsChunk<MT>;
     static std::atomic<bool> configured{false};
     if (!configured.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW, FOLD, NW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_rows_kernel<MT, RTW, FOLD, NW, FUSE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return e;
         configured.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm_rows_kernel<MT, RTW, FOLD, NW>), dim3(static_cast<unsigned>((items + NW * RTW - 1) / (NW * RTW))),
+    hipLaunchKernelGGL((gemm_rows_kernel<MT, RTW, FOLD, NW, FUSE>), dim3(static_cast<unsigned>((items + NW * RTW - 1) / (NW * RTW))),
                        dim3(64 * NW), lds, stream, plan, M);
     return hipGetLastError();
 }
@@ -1795,7 +1797,7 @@ ptqtp_status ptqtp_gemv_batch(const void *plan, int64_t items, void *stream_) {
     return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
 }
 
-ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *stream_) {
+static ptqtp_status run_gemm_batch(const void *plan, int64_t items, int64_t M, void *stream_, bool fuse_planes) {
     if (!plan) return PTQTP_ERR_NULL;
     if (!aligned(plan, 256)) return PTQTP_ERR_ALIGN;
     if (items <= 0 || items > (1ll << 30) || M < 1 || M > PTQTP_GEMM_SMALL_MAX_M) return PTQTP_ERR_SHAPE;
@@ -1812,7 +1814,13 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
         // `rows`: 1, 2, 4 = row tiles per wave of a four-wave workgroup; 8 = two per wave, eight waves.
         const int rows = g_tune_small_rows ? g_tune_small_rows : (M <= 16 ? 4 : 8);
         const bool fold = g_tune_small_fold < 0 ? M > 32 : g_tune_small_fold != 0;   // measured on the 8B stack
-        if (rows == 8) {
+        if (fuse_planes && M > 32) {
+            // the weight rebuilt in fp16 per 32-column field, one MFMA pass instead of one per plane (8B stack,
+            // 64 tokens: 1433 -> 1131 us; 48: 1198 -> 993 us); up to 32 tokens the matrix pipe is not what binds
+            e = M <= 48 ? launch_gemm_rows<3, 2, true, 8, true>(ph, items, Mi, stream)
+                        : launch_gemm_rows<4, 2, true, 8, true>(ph, items, Mi, stream);
+        }
+        else if (rows == 8) {
             if (M <= 16) e = launch_gemm_rows<1, 2, false, 8>(ph, items, Mi, stream);
             else if (M <= 32) e = fold ? launch_gemm_rows<2, 2, true, 8>(ph, items, Mi, stream)
                                        : launch_gemm_rows<2, 2, false, 8>(ph, items, Mi, stream);
@@ -1838,6 +1846,14 @@ ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *
                         : launch_gemm_rows<4, 2, false>(ph, items, Mi, stream);
     }
     return e == hipSuccess ? PTQTP_OK : PTQTP_ERR_HIP;
+}
+
+ptqtp_status ptqtp_gemm_batch(const void *plan, int64_t items, int64_t M, void *stream) {
+    return run_gemm_batch(plan, items, M, stream, false);
+}
+
+ptqtp_status ptqtp_gemm_batch_fused(const void *plan, int64_t items, int64_t M, void *stream) {
+    return run_gemm_batch(plan, items, M, stream, true);
 }
 
 ptqtp_status ptqtp_tune(const char *key, int32_t value) {

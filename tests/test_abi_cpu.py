@@ -30,7 +30,7 @@ def test_header_symbols_exported(lib):
     assert {"ptqtp_pack", "ptqtp_unpack", "ptqtp_gemv", "ptqtp_gemm_small", "ptqtp_packed_bytes",
             "ptqtp_workspace_bytes", "ptqtp_status_string", "ptqtp_version", "ptqtp_tune", "ptqtp_gemm",
             "ptqtp_gemv_batch", "ptqtp_gemv_batch_plan", "ptqtp_batch_items", "ptqtp_batch_plan_bytes",
-            "ptqtp_quantize", "ptqtp_quantize_workspace_bytes", "ptqtp_gemm_batch", "ptqtp_chain_plan_bytes",
+            "ptqtp_quantize", "ptqtp_quantize_workspace_bytes", "ptqtp_gemm_batch", "ptqtp_gemm_batch_fused", "ptqtp_chain_plan_bytes",
             "ptqtp_chain_plan", "ptqtp_chain_run", "ptqtp_chain_run_batch", "ptqtp_gemm_route", "ptqtp_check_blob",
             "ptqtp_quantize_static"} <= set(names)
     for n in names:

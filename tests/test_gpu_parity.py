@@ -300,6 +300,76 @@ def test_gemm_batch_integer_exact_bitwise(ptq, M):
             assert np.array_equal(ent[2].cpu().numpy().astype(np.float64), y_ref), f"fold={fold}"
 
 
+@pytest.mark.parametrize("M", [33, 40, 48, 49, 64])
+def test_gemm_batch_fused_matches_rounded_weight_oracle(ptq, M):
+    # ptqtp_gemm_batch_fused from 33 tokens on: the layer of the weights rounded once to fp16 (tight gate), inside the
+    # bar of the unfused layer, and really another arithmetic than ptqtp_gemm_batch
+    shapes = [(200, 2304), (7, 640), (1024, 1024), (33, 14336), (16, 128), (528, 4096)]
+    lins, xs, entries = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        lin = workloads.make_linear(N, K, 76, i)
+        x = workloads.make_x(M, K, 76, i, M)
+        y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+        lins.append(lin); xs.append(x)
+        entries.append((pack(ptq, lin), dev(x), y, N, K))
+    plan = ptq.ptqtp_gemv_batch_plan(entries)
+    ptq.ptqtp_gemm_batch(plan, M)
+    plain = [ent[2].clone() for ent in entries]
+    for ent in entries:
+        ent[2].fill_(float("nan"))
+    for rep in range(2):
+        ptq.ptqtp_gemm_batch_fused(plan, M)
+    differs = False
+    for lin, x, ent, y_plain in zip(lins, xs, entries, plain):
+        ref_f, B_f = oracle.forward_fused(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
+        ref, B = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+        got = ent[2].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - ref_f) <= TIGHT * B_f), f"{(np.abs(got - ref_f) / np.maximum(B_f, 1e-300)).max():.3e}"
+        assert np.all(np.abs(got - ref) <= TOL * B)
+        assert np.all(np.abs(got - ref) <= (2.0 ** -11 + TIGHT) * B)
+        differs = differs or not torch.equal(ent[2], y_plain)
+    assert differs
+    # fp16 outputs
+    ents16 = [(e[0], e[1], torch.empty((M, e[3]), dtype=torch.float16, device="cuda:0"), e[3], e[4]) for e in entries]
+    plan16 = ptq.ptqtp_gemv_batch_plan(ents16, y_dtype=ptq.PTQTP_F16)
+    ptq.ptqtp_gemm_batch_fused(plan16, M)
+    for lin, x, ent in zip(lins, xs, ents16):
+        ref_f, B_f = oracle.forward_fused(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x)
+        got = ent[2].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - ref_f) <= TIGHT_F16 * B_f + 2.0 ** -25)
+
+
+def test_gemm_batch_fused_small_m_and_integer_exact(ptq):
+    # up to 32 tokens the fused call is ptqtp_gemm_batch bit for bit; on inputs whose weights and partial sums are
+    # exactly representable the fused arithmetic returns the oracle's bits at every M
+    shapes = [(208, 3072), (40, 14336), (129, 256)]
+    for M in (1, 2, 16, 17, 32, 33, 64):
+        cases, entries = [], []
+        for i, (N, K) in enumerate(shapes):
+            lin, x = workloads.integer_exact_case(N, K, M, 77, i)
+            y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+            cases.append((lin, x)); entries.append((pack(ptq, lin), dev(x), y, N, K))
+        plan = ptq.ptqtp_gemv_batch_plan(entries)
+        ptq.ptqtp_gemm_batch_fused(plan, M)
+        for (lin, x), ent in zip(cases, entries):
+            y_ref, _ = oracle.forward(lin["T1"], lin["T2"], lin["a1"], lin["a2"], x, threads=8)
+            assert np.array_equal(ent[2].cpu().numpy().astype(np.float64), y_ref), M
+    for M in (2, 16, 32):
+        ents, lins = [], []
+        for i, (N, K) in enumerate([(200, 2304), (33, 640)]):
+            lin = workloads.make_linear(N, K, 78, i)
+            ents.append((pack(ptq, lin), dev(workloads.make_x(M, K, 78, i, M)),
+                         torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0"), N, K))
+        plan = ptq.ptqtp_gemv_batch_plan(ents)
+        ptq.ptqtp_gemm_batch(plan, M)
+        plain = [e[2].clone() for e in ents]
+        ptq.ptqtp_gemm_batch_fused(plan, M)
+        for e, y_plain in zip(ents, plain):
+            assert torch.equal(e[2], y_plain), M
+    with pytest.raises(ptq.PtqtpError):
+        ptq.ptqtp_gemm_batch_fused(plan, 65)
+
+
 def test_gemv_zero_bound_gives_exact_zero(ptq):
     N, K = 64, 512
     lin = workloads.make_linear(N, K, 57)
