@@ -346,7 +346,9 @@ ptqtp_status ptqtp_gemm_route(int64_t M, int64_t N, int64_t K, int32_t group, in
  * device-side plan, 0 = default: levels of up to four stages carry their descriptors as kernel arguments), "batch_rows_kernel" (ptqtp_gemm_batch: 0 = per-wave activation loads, -1/1 = shared activation tile),
  * "small_fold" (ptqtp_gemm_batch with two row tiles per wave: 1 = multiply the group scales into the
  * expanded trits before the matrix pipe, 0 = rescale the per-group sums after it, -1 = default: before for
- * more than 32 tokens), "tile" (1 = use an MFMA tile for every batch > 1, -1 = never below 256 tokens,
+ * more than 32 tokens), "small_ahead" (one linear at 17..64 tokens, up to two row tiles per item: 1 = the item
+ * kernel whose loads run one step ahead of its arithmetic, 0 = the plain one, -1 = default: by shape),
+ * "tile" (1 = use an MFMA tile for every batch > 1, -1 = never below 256 tokens,
  * 0 = default: by cost model from 33 tokens on), "tile_variant" (workgroup tile, rows x tokens: 1 = 256 x 128, 2 = 128 x 128, 3 = 256 x 256, 4 = 128 x 64, 5 = 64 x 64,
  * 0 = default: the cheapest by a cost model of the problem size; also honoured by ptqtp_chain_run_batch
  * above PTQTP_GEMM_SMALL_MAX_M tokens where the stage allows the tile);

@@ -485,8 +485,11 @@ __device__ __forceinline__ int slot_rd_off(int nl, int q, int f) { return nl * k
 
 // PLAN: the item list of a batch plan (R must be 1): one launch over many linears, all with M tokens.
 // ML = load instructions per 16-token tile (1, 2, 4 or 8): covers M <= 2*ML when MT == 1.
+// (MT, R) whose registers fit two waves per SIMD (256 per lane): those run with up to eight waves per item
+constexpr bool items_eight_waves(int MT, int R) { return MT * R < 6 || (MT == 2 && R == 4); }
+
 template <int MT, int R, int S, bool PLAN, int ML>
-__global__ void __launch_bounds__(MT * R >= 6 ? 256 : 512)
+__global__ void __launch_bounds__(items_eight_waves(MT, R) ? 512 : 256)
 gemm_items_kernel(const PlanHeader *__restrict__ plan, const uint8_t *__restrict__ records_,
                   const uint16_t *__restrict__ x_, void *__restrict__ y_, int M, int N_, int K_, int RT_, int KS_,
                   int y_f16_, const uint16_t *__restrict__ residual, int gated)
@@ -1180,12 +1183,12 @@ hipError_t launch_gemm_items_ml(const PlanHeader *plan, const uint8_t *records, 
 
 template <int MT, int R, int S>
 hipError_t launch_gemm_items(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
-                             hipStream_t stream, const uint16_t *residual = nullptr, int gated = 0)
+                             hipStream_t stream, const uint16_t *residual = nullptr, int gated = 0, int waves = 0)
 {
     // measured: 8 waves per item, except for the register-heavy 64-token x 2-tile case: 2 waves there on 8B shapes
     // (K = 4096), 4 on longer rows (70B down, K = 28672, at 64 tokens: 166 -> 105 us)
-    int W = g_tune_small_waves > 0 ? g_tune_small_waves : (MT * R >= 6 ? (s.KS > 16 ? 4 : 2) : 8);
-    if (W > (MT * R >= 6 ? 4 : 8)) W = MT * R >= 6 ? 4 : 8;
+    int W = g_tune_small_waves > 0 ? g_tune_small_waves : waves > 0 ? waves : (MT * R >= 6 ? (s.KS > 16 ? 4 : 2) : 8);
+    if (W > (items_eight_waves(MT, R) ? 8 : 4)) W = items_eight_waves(MT, R) ? 8 : 4;
     while (W > 1 && W > s.KS) W /= 2;
     const int64_t grid = gated ? s.RT / 2 : (s.RT + R - 1) / R;
     return launch_gemm_items_ml<MT, R, S, false>(nullptr, records, x, y, M, static_cast<int>(s.N), static_cast<int>(s.K),
@@ -1433,6 +1436,188 @@ hipError_t launch_gemm_rows(const PlanHeader *plan, int64_t items, int M, hipStr
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// small-batch item kernel with its loads one step ahead of the arithmetic
+// ------------------------------------------------------------------------------------------
+// One linear per launch has too few items to hide a DRAM round trip behind other workgroups (70B gate at 32
+// tokens: 1.75 waves per SIMD), so here a wave hides it behind its own arithmetic.  Item, wave roles, rotated
+// start, final reduction and epilogue are those of gemm_items_kernel; what differs is the K loop: the step's
+// activations go from global memory straight into the wave's LDS slot (global_load_lds_dwordx4 in the chunk
+// layout of gemm_rows_kernel: no staging registers), and as soon as the wave has read its MFMA operands out of
+// the slot it issues the next step's activation loads into the same slot and the next step's records into a
+// second register set; both are in flight while the MFMAs of the present step run.
+// A wave's LDS reads are not ordered against its own later direct-to-LDS loads (the data comes back on another
+// path), hence the wait for the operand reads before the next loads are issued.
+template <int MT, int R>
+__global__ void __launch_bounds__(items_eight_waves(MT, R) ? 512 : 256)
+gemm_items_ahead_kernel(const uint8_t *__restrict__ records, const uint16_t *__restrict__ x, void *__restrict__ y,
+                        int M, int N, int K, int RT, int KS, int y_f16, const uint16_t *__restrict__ residual, int gated)
+{
+    extern __shared__ float red[];                     // [W][R][MT][16 tokens][16 rows]; first used as activation slots
+    constexpr int kChunk = kRowsChunk<MT>;
+    constexpr int kSlot = ((MT + 1) / 2) * 16 * kChunk;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int W = blockDim.x >> 6;
+    const int nl = lane & 15, q = lane >> 4;
+    const int rstride = gated ? RT / 2 : 1;
+    const int rt0 = gated ? blockIdx.x : blockIdx.x * R;
+    const int rot = (rt0 * 5) % KS;
+
+    float yacc[R][MT][4];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) yacc[r][mt][j] = 0.f;
+
+    char *slot = reinterpret_cast<char *>(red) + w * kSlot;
+    const char *xop = slot + nl * kChunk + q * 16;
+
+    struct Recs { uintx4 p1[R], p2[R]; uintx2 sc[R]; };
+    auto step_of = [&](int ks) { const int kse = ks + rot; return kse >= KS ? kse - KS : kse; };
+    auto load_recs = [&](Recs &c, int kse) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int rt = rt0 + r * rstride < RT ? rt0 + r * rstride : rt0;
+            const uint8_t *rec = records + (static_cast<size_t>(rt) * KS + kse) * kRecordBytes;
+            c.p1[r] = load_stream<uintx4>(rec + lane * 16);
+            c.p2[r] = load_stream<uintx4>(rec + kPlaneBytes + lane * 16);
+            c.sc[r] = load_stream<uintx2>(rec + 2 * kPlaneBytes + nl * 8);
+        }
+    };
+    // chunk c = 1 KiB = 512 B of token t0(c) and of token t0(c) + 16 (one token with up to 16 tokens)
+    auto stage = [&](int kse) {
+        constexpr int NCH = 16 * ((MT + 1) / 2);
+        int kc = kse * kStepK + (lane & 31) * 8;
+        kc = kc < K ? kc : kc - 128;                 // padded half record: its trits are zero
+        if (MT > 1 || lane < 32) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int t0 = (c >> 4) * 32 + (c & 15);
+                if (t0 < M) {                        // uniform: chunks of tokens that do not exist are not loaded
+                    int m = t0 + (lane >> 5) * 16;
+                    m = m < M ? m : M - 1;           // second token past M: a duplicate, never stored
+                    asm volatile("" : "+v"(m));      // keep the row address out of loop-invariant registers
+                    lds_direct_load16(x + static_cast<size_t>(m) * K + kc, slot + c * kChunk);
+                }
+            }
+        }
+    };
+    uintx4 xa[MT][8];
+    auto operands = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the step's activations are in the slot, its records in registers
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int f = 0; f < 8; ++f)
+                xa[mt][f] = *reinterpret_cast<const uintx4 *>(xop + rows_operand_offset<MT>(mt, f));
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // the slot may be overwritten from here on
+    };
+    auto compute = [&](const Recs &c) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float a1g0 = half_bits_to_float(c.sc[r].x & 0xffffu), a1g1 = half_bits_to_float(c.sc[r].x >> 16);
+            const float a2g0 = half_bits_to_float(c.sc[r].y & 0xffffu), a2g1 = half_bits_to_float(c.sc[r].y >> 16);
+            floatx4 acc[MT];
+            group_sum<MT, 0>(xa, c.p1[r], acc);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) yacc[r][mt][j] = fmaf(a1g0, acc[mt][j], yacc[r][mt][j]);
+            group_sum<MT, 1>(xa, c.p1[r], acc);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) yacc[r][mt][j] = fmaf(a1g1, acc[mt][j], yacc[r][mt][j]);
+            group_sum<MT, 0>(xa, c.p2[r], acc);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) yacc[r][mt][j] = fmaf(a2g0, acc[mt][j], yacc[r][mt][j]);
+            group_sum<MT, 1>(xa, c.p2[r], acc);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) yacc[r][mt][j] = fmaf(a2g1, acc[mt][j], yacc[r][mt][j]);
+        }
+    };
+
+    Recs ra, rb;
+    int ks = w;                                        // this wave's steps: w, w + W, ...
+    if (ks < KS) { stage(step_of(ks)); load_recs(ra, step_of(ks)); }
+    while (ks < KS) {
+        operands();
+        if (ks + W < KS) { stage(step_of(ks + W)); load_recs(rb, step_of(ks + W)); }
+        compute(ra);
+        ks += W;
+        if (ks >= KS) break;
+        operands();
+        if (ks + W < KS) { stage(step_of(ks + W)); load_recs(ra, step_of(ks + W)); }
+        compute(rb);
+        ks += W;
+    }
+
+    constexpr int OUT = R * MT * 256;
+    __syncthreads();                                   // the slots are dead: the space becomes `red`
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                red[w * OUT + ((r * MT + mt) * 16 + 4 * q + j) * 16 + nl] = yacc[r][mt][j];
+    __syncthreads();
+    const int n_out = gated ? N / 2 : N;              // gated: silu(gate) * up, one output per (gate, up) row pair
+    for (int o = threadIdx.x; o < (gated ? OUT / R : OUT); o += blockDim.x) {
+        float s = 0.f;
+        for (int ww = 0; ww < W; ++ww) s += red[ww * OUT + o];
+        const int on = o & 15, t = o >> 4;
+        const int m = (t / 16 % MT) * 16 + (t & 15), r = t / (16 * MT);
+        const int n = (rt0 + r) * kTileRows + on;
+        if (m < M && rt0 + r * rstride < RT && n < n_out) {
+            if (gated) {
+                float u = 0.f;
+                for (int ww = 0; ww < W; ++ww) u += red[ww * OUT + o + MT * 256];
+                s = (s / (1.0f + __expf(-s))) * u;
+            }
+            const size_t off = static_cast<size_t>(m) * n_out + n;
+            if (residual != nullptr) s += half_bits_to_float(load_global<uint16_t>(residual + off));
+            if (y_f16) reinterpret_cast<_Float16 *>(y)[off] = static_cast<_Float16>(s);
+            else reinterpret_cast<float *>(y)[off] = s;
+        }
+    }
+}
+
+int g_tune_small_ahead = -1;
+
+template <int MT, int R>
+hipError_t launch_gemm_items_ahead(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int y_f16,
+                                   hipStream_t stream, const uint16_t *residual, int gated, int waves)
+{
+    constexpr int kSlot = ((MT + 1) / 2) * 16 * kRowsChunk<MT>;
+    constexpr int kMaxLds = 8 * 16 * kRowsChunk<2>;             // eight slots of 32 tokens = four of 64
+    constexpr int kMaxW = (!items_eight_waves(MT, R) || MT > 2) ? 4 : 8;
+    int W = g_tune_small_waves > 0 ? g_tune_small_waves : waves > 0 ? waves : (MT * R >= 6 ? (s.KS > 16 ? 4 : 2) : 8);
+    if (W > kMaxW) W = kMaxW;
+    while (W > 1 && W > s.KS) W /= 2;
+    size_t lds = static_cast<size_t>(W) * R * MT * 256 * sizeof(float);
+    if (lds < static_cast<size_t>(W) * kSlot) lds = static_cast<size_t>(W) * kSlot;
+    static std::atomic<bool> configured{false};
+    if (!configured.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_items_ahead_kernel<MT, R>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+        if (e != hipSuccess) return e;
+        configured.store(true, std::memory_order_release);
+    }
+    const int64_t grid = gated ? s.RT / 2 : (s.RT + R - 1) / R;
+    hipLaunchKernelGGL((gemm_items_ahead_kernel<MT, R>), dim3(static_cast<unsigned>(grid)), dim3(W * 64), lds, stream,
+                       records, x, y, M, static_cast<int>(s.N), static_cast<int>(s.K), static_cast<int>(s.RT),
+                       static_cast<int>(s.KS), y_f16, residual, gated);
+    return hipGetLastError();
+}
+
 // 2..64 tokens: the small-batch item kernel in the shape that measured best
 hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int M, const Shape &s, int f16,
                         hipStream_t stream, const uint16_t *residual = nullptr, int gated = 0)
@@ -1441,15 +1626,36 @@ hipError_t launch_small(const uint8_t *records, const uint16_t *x, void *y, int 
     // many row tiles, and always for 17..32 tokens; one otherwise (R = 4 exists for up to 32 tokens)
     int R = s.RT >= 512 ? 2 : 1;
     if (M > 16 && M <= 32) R = 2;
-    // four on the widest layers, where items are plentiful and the activations re-read per item weigh most
-    // (70B gate, 28672 rows: 16 tokens 31.8 -> 29.7 us, 32 tokens 53 -> 44 us; slower on every narrower layer)
+    // four on wide layers, where items are plentiful and the activations re-read per item weigh most (70B gate,
+    // 28672 rows: 16 tokens 31.8 -> 29.7 us, 32 tokens 53 -> 44 us; 8B gate, 14336 rows, 17..32 tokens as eight
+    // waves: 17.1 -> 14.5 us; slower on every narrower layer)
     if (s.RT >= 1536 && M >= 16 && M <= 32) R = 4;
-    if (g_tune_small_rows > 0) R = g_tune_small_rows;
-    if (gated) R = 2;                                  // a (gate tile, up tile) pair per item
+    int waves = 0;                                     // 0: the launcher's own rule
+    if (s.RT >= 768 && s.RT < 1536 && M > 16 && M <= 32) { R = 4; waves = 8; }
+    // the kernel with its loads one step ahead, where it measured faster: 17..32 tokens on layers of few row tiles
+    // as one tile per item and eight waves (8B q 9.1 -> 7.6 us, 8B down 23.2 -> 18.0 us, 70B k 14.3 -> 10.9 us),
+    // 33..64 tokens on layers of 512..1024 row tiles with long rows (70B q at 64 tokens 33.7 -> 30.8 us, 70B down
+    // 105 -> 91 us); equal or slower elsewhere (everything up to 16 tokens, 8B shapes above 32)
+    bool ahead = false;
+    if (g_tune_small_ahead != 0 && !gated) {
+        if (M > 16 && M <= 32 && s.RT < 512) { ahead = true; R = 1; waves = 8; }
+        if (M > 32 && s.RT >= 512 && s.RT <= 1024 && s.KS >= 32) { ahead = true; R = 2; }
+    }
+    if (g_tune_small_rows > 0) { R = g_tune_small_rows; waves = 0; }
+    if (gated) { R = 2; waves = 0; }                   // a (gate tile, up tile) pair per item
+    if (g_tune_small_ahead >= 0) ahead = g_tune_small_ahead == 1;
+    if (ahead && M > 16 && R <= 2) {
+        if (M <= 32) return R == 2 ? launch_gemm_items_ahead<2, 2>(records, x, y, M, s, f16, stream, residual, gated, waves)
+                                   : launch_gemm_items_ahead<2, 1>(records, x, y, M, s, f16, stream, residual, gated, waves);
+        if (M <= 48) return R == 2 ? launch_gemm_items_ahead<3, 2>(records, x, y, M, s, f16, stream, residual, gated, waves)
+                                   : launch_gemm_items_ahead<3, 1>(records, x, y, M, s, f16, stream, residual, gated, waves);
+        return R == 2 ? launch_gemm_items_ahead<4, 2>(records, x, y, M, s, f16, stream, residual, gated, waves)
+                      : launch_gemm_items_ahead<4, 1>(records, x, y, M, s, f16, stream, residual, gated, waves);
+    }
     if (M <= 16) return R == 4 ? launch_gemm_items<1, 4, 1>(records, x, y, M, s, f16, stream, residual, gated)
                       : R == 2 ? launch_gemm_items<1, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
                                : launch_gemm_items<1, 1, 2>(records, x, y, M, s, f16, stream, residual, gated);
-    if (M <= 32) return R == 4 ? launch_gemm_items<2, 4, 1>(records, x, y, M, s, f16, stream, residual, gated)
+    if (M <= 32) return R == 4 ? launch_gemm_items<2, 4, 1>(records, x, y, M, s, f16, stream, residual, gated, waves)
                       : R == 2 ? launch_gemm_items<2, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
                                : launch_gemm_items<2, 1, 1>(records, x, y, M, s, f16, stream, residual, gated);
     if (M <= 48) return R == 2 ? launch_gemm_items<3, 2, 1>(records, x, y, M, s, f16, stream, residual, gated)
@@ -1871,6 +2077,11 @@ ptqtp_status ptqtp_tune(const char *key, int32_t value) {
     if (!strcmp(key, "chain_table")) {
         if (value < 0 || value > 1) return PTQTP_ERR_SHAPE;
         ptqtp_detail::g_chain_table = value;
+        return PTQTP_OK;
+    }
+    if (!strcmp(key, "small_ahead")) {
+        if (value < -1 || value > 1) return PTQTP_ERR_SHAPE;
+        g_tune_small_ahead = value;
         return PTQTP_OK;
     }
     if (!strcmp(key, "small_fold")) {

@@ -451,18 +451,26 @@ def test_gemm_small_shapes(ptq, N, K, M):
     check(ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K), lin, x)
 
 
+@pytest.mark.parametrize("ahead", [0, 1])
 @pytest.mark.parametrize("rows,waves", [(1, 1), (1, 8), (2, 2), (2, 4), (2, 8), (4, 1), (4, 4), (4, 8)])
-def test_gemm_small_launch_shapes(ptq, rows, waves):
+def test_gemm_small_launch_shapes(ptq, rows, waves, ahead):
+    # every (row tiles per item, waves per item) of both small-batch item kernels (ahead: loads one step ahead of the
+    # arithmetic, from 17 tokens and up to two row tiles per item; elsewhere the setting falls back to the other kernel)
     try:
         ptq.ptqtp_tune("small_rows", rows)
         ptq.ptqtp_tune("small_waves", waves)
-        for N, K, M in [(200, 2304, 9), (1000, 640, 33), (48, 4096, 64), (8200, 256, 5), (1000, 640, 20)]:
+        ptq.ptqtp_tune("small_ahead", ahead)
+        for N, K, M in [(200, 2304, 9), (1000, 640, 33), (48, 4096, 64), (8200, 256, 5), (1000, 640, 20), (130, 896, 47)]:
             lin = workloads.make_linear(N, K, 65, N)
             x = workloads.make_x(M, K, 65, N)
-            check(ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K), lin, x)
+            y = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K)
+            check(y, lin, x)
+            y16 = ptq.ptqtp_gemm_small(pack(ptq, lin), dev(x), N, K, y_dtype=ptq.PTQTP_F16)
+            check(y16, lin, x, tight=TIGHT_F16)
     finally:
         ptq.ptqtp_tune("small_rows", 0)
         ptq.ptqtp_tune("small_waves", 0)
+        ptq.ptqtp_tune("small_ahead", -1)
 
 
 # ---------------------------------------------------------------- MFMA tile (large batch / prefill)
@@ -801,6 +809,10 @@ def test_gemv_70b_shapes_sampled(ptq, name):
     _sampled_rows_check(ptq, lin, x32, y32, rows[:96])
     y32b = ptq.ptqtp_gemm(packed, dev(x32), N, K)                 # the dispatching entry point takes the same route
     assert torch.equal(y32b, y32)
+    # 48 and 64 tokens through the small-batch entry point (on q and down: the kernel with its loads one step ahead)
+    for M in (48, 64):
+        xm = workloads.x_for(name, M, K, config=4)
+        _sampled_rows_check(ptq, lin, xm, ptq.ptqtp_gemm_small(packed, dev(xm), N, K), rows[:64])
 
 
 @pytest.mark.parametrize("N,K", [(262144, 128), (16, 262144), (1, 128), (100000, 384)])
