@@ -217,6 +217,12 @@ def test_gemm_batch_matches_oracle(ptq, M):
             ptq.ptqtp_tune("small_fold", -1)
         for lin, x, ent in zip(lins, xs, entries):
             check(ent[2], lin, x)
+    # fp16 outputs
+    ents16 = [(e[0], e[1], torch.full((M, e[3]), float("nan"), dtype=torch.float16, device="cuda:0"), e[3], e[4]) for e in entries]
+    plan16 = ptq.ptqtp_gemv_batch_plan(ents16, y_dtype=ptq.PTQTP_F16)
+    ptq.ptqtp_gemm_batch(plan16, M)
+    for lin, x, ent in zip(lins, xs, ents16):
+        check(ent[2], lin, x, tight=TIGHT_F16)
 
 
 def test_batch_plans_replay_from_a_graph(ptq):
