@@ -344,7 +344,7 @@ def main() -> int:
     gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
     launch_us = ms_per_step * 1e3 / launches_step
     bytes_launch = bytes_step / launches_step
-    kernel = {"batch": "gemv_items_kernel<true, 2>", "chain": "chain_items_kernel (one launch per level; launch gaps included)",
+    kernel = {"batch": "gemv_items_kernel<true, 2>", "chain": "chain_level_kernel (one launch per level; launch gaps included)",
               "fused4": "gemv_items_kernel<true, 1>"}.get(args.mode, "gemv_items_kernel<false, 1>")
     step_what = {"batch": "one pass over the stack's 7 x layers linears, every input known in advance (one launch)",
                  "chain": "one dependent decode step (4 fused stages per layer)"}.get(args.mode, "one pass over the stack, " + args.mode)
