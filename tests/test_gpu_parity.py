@@ -856,19 +856,30 @@ def test_batch_full_stack_as_benchmarked_sampled(ptq):
         N = lin["N"]
         rows = np.unique(np.concatenate([np.arange(0, 16), np.arange(N - 16, N), rng.integers(0, N, 96)]))
         _sampled_rows_check(ptq, lin, xs[i].cpu().numpy()[None, :], ys[i], rows)
-    # the same stack at 16 tokens per linear through the batched small-batch kernel
-    M = 16
-    xm = [torch.from_numpy(workloads.x_for(name, M, k, 2, layer)).to(dev0) for (layer, name), (n, k) in zip(jobs, dims)]
-    ym = [torch.full((M, n), float("nan"), dtype=torch.float32, device=dev0) for (n, k) in dims]
-    planm = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xm, ym, dims)])
-    ptq.ptqtp_gemm_batch(planm, M)
-    torch.cuda.synchronize()
-    assert all(bool(torch.isfinite(y).all()) for y in ym)
-    for layer, name in picks[1::2]:
-        i = jobs.index((layer, name))
-        lin = workloads.linear_8b(name, layer)
-        rows = np.unique(rng.integers(0, lin["N"], 64))
-        _sampled_rows_check(ptq, lin, xm[i].cpu().numpy(), ym[i], rows)
+    # the same stack at 4, 16 and 64 tokens per linear through the batched small-batch kernels, and at 64 tokens with
+    # the planes summed in fp16 before the matrix pipe: the launches bench.py times beside the headline
+    for M, fused in ((4, False), (16, False), (64, False), (64, True)):
+        xm = [torch.from_numpy(workloads.x_for(name, M, k, 2, layer)).to(dev0) for (layer, name), (n, k) in zip(jobs, dims)]
+        ym = [torch.full((M, n), float("nan"), dtype=torch.float32, device=dev0) for (n, k) in dims]
+        planm = ptq.ptqtp_gemv_batch_plan([(b, x, y, n, k) for b, x, y, (n, k) in zip(blobs, xm, ym, dims)])
+        if fused:
+            ptq.ptqtp_gemm_batch_fused(planm, M)
+        else:
+            ptq.ptqtp_gemm_batch(planm, M)
+        torch.cuda.synchronize()
+        assert all(bool(torch.isfinite(y).all()) for y in ym)
+        for layer, name in picks[1::2]:
+            i = jobs.index((layer, name))
+            lin = workloads.linear_8b(name, layer)
+            rows = np.unique(np.concatenate([np.arange(lin["N"] - 16, lin["N"]), rng.integers(0, lin["N"], 48)]))
+            xh = xm[i].cpu().numpy()
+            if not fused:
+                _sampled_rows_check(ptq, lin, xh, ym[i], rows)
+            else:
+                ref, B = oracle.forward_fused(lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows], xh)
+                err = np.abs(ym[i].cpu().numpy().astype(np.float64)[:, rows] - ref)
+                assert np.all(err <= TIGHT * B), f"{(err / B).max():.3e}"
+        del xm, ym, planm
 
 
 def test_smoke_entry(ptq):
