@@ -580,15 +580,17 @@ def test_gemm_tile_integer_exact_and_general_scales(ptq):
     check(ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K), lin, x, tight=3e-5)
 
 
-@pytest.mark.parametrize("name,flag,M", [("k", 0, 2048), ("q", 0, 2048), ("q", 16, 2048), ("q", 0, 8192), ("down", 16, 4096)])
+@pytest.mark.parametrize("name,flag,M", [("k", 0, 2048), ("q", 0, 2048), ("q", 16, 2048), ("q", 0, 8192), ("down", 16, 4096),
+                                         ("gate", 0, 2048), ("down", 0, 2048)])
 def test_gemm_tile_prefill_70b_sampled(ptq, name, flag, M):
     # prefill M = 2048 .. 8192 on 70B-shaped projections (k: 1024 rows, a small tile; q: 8192 rows, the 256 x 256 tile,
-    # also with fused planes); sampled rows and tokens against the oracle
+    # also with fused planes; gate and down at 2048 tokens: the launches of the benchmark line, gate as 256 x 256
+    # tiles for the first row blocks and a smaller tile for the rest); sampled rows and tokens against the oracle
     lin = workloads.linear_70b(name)
     N, K = lin["N"], lin["K"]
     x = workloads.x_for(name, M, K, config=4)
     y = ptq.ptqtp_gemm(pack(ptq, lin), dev(x), N, K, y_dtype=flag)
-    rows = np.unique(np.concatenate([[0, 15, N - 1], np.random.default_rng(4).integers(0, N, 48)]))
+    rows = np.unique(np.concatenate([[0, 15, N - 1, N - 16, N - 257], np.random.default_rng(4).integers(0, N, 48)]))
     toks = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 255, 256, 2047, M - 1], np.random.default_rng(5).integers(0, M, 24)]))
     sub = (lin["T1"][rows], lin["T2"][rows], lin["a1"][rows], lin["a2"][rows])
     ref, B = oracle.forward(*sub, x[toks], threads=8)
