@@ -40,9 +40,10 @@
  * between the norm and its square.  A further test plants one mistake at a time in a copy of this
  * file (a dropped term, a wrong sign or index, a changed constant) and requires a pin to fail.
  * What the paper leaves open (the order of the lambda update, the order of ties, which of the two
- * stopping rules) is a reading, not a pin.  The cap lambda_max = 1 is carried from the paper but
- * cannot be reached from the prescribed start at G = 128 (one raise multiplies lambda by
- * sqrt(kappa / 1e6), and kappa is about 2G / lambda): no input exercises it.
+ * stopping rules) is a reading, not a pin.  The cap lambda_max = 1 cannot be reached from the
+ * prescribed start at G = 128 (one raise multiplies lambda by sqrt(kappa / 1e6), and kappa is about
+ * 2G / lambda: the fixed point is 2G / 1e6); it is pinned on one unit of 2^20 equal weights, where
+ * T1 = T2 stays a fixed point of the search and lambda climbs from 1e-8 to the cap in five raises.
  */
 #include <math.h>
 #include <stddef.h>

@@ -68,6 +68,10 @@ MUTATIONS = [
      "if (!(kappa < 1.0e6)) {", "if (!(kappa < 1.0e12)) {"),
     ("ptqtp_quantizer_oracle.c", "test_quantizer_oracle_pins", "regularisation grows with kappa instead of its square root",
      "const double grow = sqrt(kappa / 1.0e6);", "const double grow = kappa / 1.0e6;"),
+    ("ptqtp_quantizer_oracle.c", "test_quantizer_oracle_pins", "regularisation capped at 2 instead of 1",
+     "if (!(nl <= 1.0)) nl = 1.0;", "if (!(nl <= 2.0)) nl = 2.0;"),
+    ("ptqtp_quantizer_oracle.c", "test_quantizer_oracle_pins", "regularisation not capped",
+     "if (!(nl <= 1.0)) nl = 1.0;", "if (nl != nl) nl = 1.0;"),
     ("ptqtp_quantizer_oracle.c", "test_quantizer_oracle_pins", "binary16 rounding towards zero",
      "if (rem > 0.5 || (rem == 0.5 && fmod(r, 2.0) == 1.0)) r += 1.0;", "if (rem > 1.5) r += 1.0;"),
     ("ptqtp_block_oracle.c", "test_block_oracle_pins", "silu with the sign of the exponent flipped",

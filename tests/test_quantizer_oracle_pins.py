@@ -198,6 +198,35 @@ def test_stopping_rule_is_the_norm_not_its_square():
     assert oracle.quantize(W, max_iters=50, eps=eps)["iters"] == by_norm
 
 
+def test_lambda_is_capped_at_one():
+    # lambda_max = 1 (hyper-parameters of the experiments; second listing).  With groups of 128 the cap is out of reach
+    # (the update has the fixed point 2G / 1e6), so the pin uses ONE unit of G = 2^20 equal weights: T1 = T2 = +1 is
+    # then a fixed point of the trit search (alpha1 + alpha2 = c reproduces every entry), A = [[G + l, G], [G, G + l]]
+    # stays as singular as l allows, and l follows l <- l * sqrt(kappa / 1e6) from 1e-8 up: 1.4e-4, 1.7e-2, 0.19, 0.63,
+    # then 1.15 -> capped.  The recurrence is rebuilt here with numpy's inverse and norms.
+    big = 1 << 20
+    c = np.float16(0.25)
+    W = np.full((1, big), c, dtype=np.float16)
+    lam, seen = 1e-8, []
+    for _ in range(8):
+        A = np.array([[big + lam, big], [big, big + lam]], dtype=np.float64)
+        kappa = np.linalg.norm(A) * np.linalg.norm(np.linalg.inv(A))
+        if not kappa < 1e6:
+            lam = min(1.0, lam * np.sqrt(kappa / 1e6))
+        seen.append(lam)
+    assert seen[3] < 1.0 and seen[4] == 1.0 and seen[-1] == 1.0        # the cap is what stops the growth
+    for t in (1, 2, 4, 5, 8):
+        q = oracle.quantize(W, group=big, max_iters=t, eps=0.0)
+        assert q["iters"] == t
+        # the cancelling determinant limits kappa, hence lambda below the cap, to ~1e-6 relative
+        assert abs(q["lam"][0, 0] - seen[t - 1]) <= 1e-5 * seen[t - 1]
+        if t >= 5:
+            assert q["lam"][0, 0] == 1.0
+        assert np.all(q["T1"] == 1) and np.all(q["T2"] == 1)
+        alpha = float(c) * big / (2.0 * big + q["lam"][0, 0])              # closed form of the ridge solve on this unit
+        assert abs(q["a1_f64"][0, 0] - alpha) <= 1e-9 * alpha and abs(q["a2_f64"][0, 0] - alpha) <= 1e-9 * alpha
+
+
 def test_double_to_half_rounding_matches_numpy():
     r = np.random.default_rng(11)
     h = np.arange(0, 0x7c00, dtype=np.uint16).view(np.float16).astype(np.float64)      # every finite binary16 value
